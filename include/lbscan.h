@@ -1,0 +1,125 @@
+/*
+ * lbscan - locally bi-directional selective scan (LBMamba, arXiv 2506.15976)
+ *          for AMD MI355X (gfx950).  C ABI, no C++ or framework types.
+ *
+ * Notation: B = batch, D = channels (the paper's E), N = state size,
+ * L = sequence length, M = window length.
+ *
+ * Per (b, d, n), with the time step of Sec. 3.1 Eq. 3 / Algorithm 1
+ *     dt_t   = softplus?(delta[b,d,t] + delta_bias[d])
+ *     abar_t = exp(dt_t * A[d,n])           u_t = dt_t * Bm[b,n,t] * x[b,d,t]
+ * the library computes
+ *     f_t = abar_t f_{t-1} + u_t,  f_{-1} = 0           global forward scan (Eq. 1)
+ *     g_t = 0 at the last step of each window [kM, kM+M-1] (and at t = L-1),
+ *           abar_t (g_{t+1} + u_{t+1}) otherwise        local backward scan (Eq. 7,
+ *           without its own input term: the "B x" counted once, Eq. 8)
+ *     y_t = sum_n Cm[b,n,t] (f_t + g_t) + Dskip[d] x_t  (Eq. 8)
+ *     out_t = y_t * SiLU(z_t) when z is given            (Algorithm 1, gate line)
+ *
+ * Memory layout: every tensor is dense with the last index contiguous:
+ *     x, delta, z, y, dout, dx, ddelta, dz : (B, D, L)     element type = dtype
+ *     Bm, Cm, dBm, dCm                     : (B, N, L)     element type = dtype
+ *     A, dA                                : (D, N)        fp32
+ *     Dskip, delta_bias and their grads    : (D)           fp32
+ * One B/C group is shared by all channels (Algorithm 1: B, C have shape
+ * (B, L, N)); A is real.
+ *
+ * Ownership: every data pointer is a caller-owned DEVICE pointer.  The library
+ * never allocates, frees or synchronises; it enqueues work on the HIP stream
+ * passed in (a hipStream_t cast to void*, NULL = default stream) and returns.
+ * Outputs are fully overwritten.  Calls are re-entrant; there is no global
+ * state besides a thread-local last-error string.
+ *
+ * Errors: 0 on success, a negative LBSCAN_E* code otherwise; nothing is
+ * enqueued when an error is returned before launch.
+ */
+#ifndef LBSCAN_H
+#define LBSCAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LBSCAN_OK            0
+#define LBSCAN_EINVAL       (-1)  /* null required pointer, negative size, window < 1        */
+#define LBSCAN_EUNSUPPORTED (-2)  /* dtype, state size or window the GPU path does not cover  */
+#define LBSCAN_EWORKSPACE   (-3)  /* workspace missing or smaller than lbscan_workspace_bytes */
+#define LBSCAN_EHIP         (-4)  /* HIP launch error; text via lbscan_last_error()           */
+
+#define LBSCAN_FP32 0
+#define LBSCAN_BF16 1
+
+#define LBSCAN_MAX_DSTATE 16
+
+typedef struct lbscan_args {
+    int32_t batch, dim, dstate, seqlen;  /* B, D, N, L; any may be 0 (then nothing is done)   */
+    int32_t window;           /* M >= 1.  GPU path: M in {1,2,4,8,16}, or any M >= L when L <= 16 */
+    int32_t dtype;            /* LBSCAN_FP32 or LBSCAN_BF16: storage type of the (B,D,L) and
+                                 (B,N,L) tensors; arithmetic is fp32 either way                */
+    int32_t delta_softplus;   /* 0/1: apply softplus to delta + delta_bias (Algorithm 1)      */
+    int32_t reverse;          /* 0: as defined above.  1: the same operator applied to the
+                                 time-reversed sequence, result reversed back (global scan
+                                 runs right to left, windows are anchored at t = L-1); this is
+                                 the per-encoder sequence reversal of Sec. 3.3 without a copy  */
+    const void  *x;           /* (B,D,L) */
+    const void  *delta;       /* (B,D,L) raw: before bias and softplus */
+    const void  *Bm;          /* (B,N,L) */
+    const void  *Cm;          /* (B,N,L) */
+    const void  *z;           /* (B,D,L) or NULL: no gate */
+    const float *A;           /* (D,N) */
+    const float *Dskip;       /* (D) or NULL: treated as 0 */
+    const float *delta_bias;  /* (D) or NULL: treated as 0 */
+    void        *y;           /* (B,D,L) out */
+    void        *workspace;   /* device scratch of lbscan_workspace_bytes() bytes, or NULL if 0 */
+    size_t       workspace_bytes;
+} lbscan_args;
+
+#define LBSCAN_WS_FWD   0
+#define LBSCAN_WS_BWD   1
+#define LBSCAN_WS_BIDIR 2
+
+/* Forward pass of the locally bi-directional scan (Sec. 3.2, Eq. 7-8, on top of
+ * the global forward scan of Eq. 1-3; gate and skip of Algorithm 1 fused in). */
+int lbscan_fwd(const lbscan_args *args, void *hip_stream);
+
+/* Gradients of lbscan_fwd with respect to every input (the paper reports only
+ * training throughput, Appendix B; the formulas are the reverse-mode derivative
+ * of the forward definition above).  fwd_args names the forward inputs
+ * (fwd_args->y is not read).  dout is the upstream gradient of out.  dz may be
+ * NULL iff fwd_args->z is NULL.  dDskip / ddelta_bias may be NULL iff the
+ * corresponding input is NULL.  All outputs are overwritten (not accumulated). */
+int lbscan_bwd(const lbscan_args *fwd_args, const void *dout,
+               void *dx, void *ddelta, void *dz,
+               void *dBm, void *dCm,
+               float *dA, float *dDskip, float *ddelta_bias,
+               void *hip_stream);
+
+/* The comparison method: global bi-directional scan (Sec. 3.1, Eq. 4-6) as two
+ * full passes over HBM.  Pass 1 scans fwd_set left to right (Eq. 1-2); pass 2
+ * scans bwd_set right to left (Eq. 4-5) and adds; each direction adds its own
+ * Dskip x term; the sum is gated once with fwd_set->z and written to
+ * fwd_set->y.  window / reverse / z / y of bwd_set are ignored.  bwd_set may
+ * alias fwd_set. */
+int lbscan_bidir_fwd(const lbscan_args *fwd_set, const lbscan_args *bwd_set, void *hip_stream);
+
+/* Bytes of device scratch the call named by `which` (LBSCAN_WS_*) needs for
+ * these sizes; 0 means workspace may be NULL. */
+size_t lbscan_workspace_bytes(const lbscan_args *args, int which);
+
+/* Window length the paper uses for a sequence length (Sec. 4, first paragraph):
+ * L > 256 -> 16, 128 < L <= 256 -> 8, otherwise 4. */
+int lbscan_default_window(int32_t seqlen);
+
+const char *lbscan_strerror(int code);
+/* Text of the last HIP error seen by this thread ("" if none). */
+const char *lbscan_last_error(void);
+/* Library version, e.g. "0.1.0". */
+const char *lbscan_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LBSCAN_H */

@@ -1,0 +1,216 @@
+"""ctypes binding of liblbscan.so: argument marshalling only.
+
+Every step of the computation runs in the HIP kernels behind the C ABI declared
+in include/lbscan.h.  PyTorch is used for device memory and the current
+stream, nothing else.  There is no CPU fallback: if the library has not been
+built, loading fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblbscan.so")
+
+LBSCAN_FP32, LBSCAN_BF16 = 0, 1
+WS_FWD, WS_BWD, WS_BIDIR = 0, 1, 2
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+
+EXPORTS = (
+    "lbscan_fwd", "lbscan_bwd", "lbscan_bidir_fwd", "lbscan_workspace_bytes",
+    "lbscan_default_window", "lbscan_strerror", "lbscan_last_error", "lbscan_version",
+)
+
+
+class LbscanArgs(ctypes.Structure):
+    """Mirror of struct lbscan_args."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("dim", ctypes.c_int32), ("dstate", ctypes.c_int32),
+        ("seqlen", ctypes.c_int32), ("window", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("delta_softplus", ctypes.c_int32), ("reverse", ctypes.c_int32),
+        ("x", ctypes.c_void_p), ("delta", ctypes.c_void_p), ("Bm", ctypes.c_void_p),
+        ("Cm", ctypes.c_void_p), ("z", ctypes.c_void_p), ("A", ctypes.c_void_p),
+        ("Dskip", ctypes.c_void_p), ("delta_bias", ctypes.c_void_p), ("y", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+class LbscanError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(what)
+
+
+_lib = None
+
+
+def load():
+    """Load liblbscan.so (once).  torch is imported first so that the library
+    binds to the HIP runtime already in the process."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2506_15976_amd.build` "
+            "(there is no CPU fallback)")
+    import torch  # noqa: F401  (loads libamdhip64 first)
+    lib = ctypes.CDLL(LIB_PATH)
+    ap = ctypes.POINTER(LbscanArgs)
+    vp = ctypes.c_void_p
+    lib.lbscan_fwd.restype = ctypes.c_int
+    lib.lbscan_fwd.argtypes = [ap, vp]
+    lib.lbscan_bidir_fwd.restype = ctypes.c_int
+    lib.lbscan_bidir_fwd.argtypes = [ap, ap, vp]
+    lib.lbscan_bwd.restype = ctypes.c_int
+    lib.lbscan_bwd.argtypes = [ap] + [vp] * 10
+    lib.lbscan_workspace_bytes.restype = ctypes.c_size_t
+    lib.lbscan_workspace_bytes.argtypes = [ap, ctypes.c_int]
+    lib.lbscan_default_window.restype = ctypes.c_int
+    lib.lbscan_default_window.argtypes = [ctypes.c_int32]
+    lib.lbscan_strerror.restype = ctypes.c_char_p
+    lib.lbscan_strerror.argtypes = [ctypes.c_int]
+    lib.lbscan_last_error.restype = ctypes.c_char_p
+    lib.lbscan_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, name: str):
+    if rc != OK:
+        lib = load()
+        msg = lib.lbscan_strerror(rc).decode()
+        if rc == EHIP:
+            msg += ": " + lib.lbscan_last_error().decode()
+        raise LbscanError(rc, f"{name} failed ({rc}): {msg}")
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return LBSCAN_FP32
+    if t.dtype == torch.bfloat16:
+        return LBSCAN_BF16
+    raise LbscanError(EUNSUPPORTED, f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def make_args(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, window,
+              delta_softplus=True, reverse=False, y=None, workspace=None):
+    """Fill a struct lbscan_args from device tensors.  Shapes: x, delta, z, y
+    (B,D,L); Bm, Cm (B,N,L); A (D,N) fp32; Dskip, delta_bias (D) fp32."""
+    import torch
+    Bsz, D, L = x.shape
+    N = A.shape[1]
+    code = _dtype_code(x)
+    for name, t, shape in (("delta", delta, (Bsz, D, L)), ("Bm", Bm, (Bsz, N, L)),
+                           ("Cm", Cm, (Bsz, N, L)), ("z", z, (Bsz, D, L)), ("y", y, (Bsz, D, L))):
+        if t is None:
+            continue
+        if tuple(t.shape) != shape or t.dtype != x.dtype:
+            raise LbscanError(EINVAL, f"{name}: expected {shape} {x.dtype}, got {tuple(t.shape)} {t.dtype}")
+    for name, t, shape in (("A", A, (D, N)), ("Dskip", Dskip, (D,)), ("delta_bias", delta_bias, (D,))):
+        if t is None:
+            continue
+        if tuple(t.shape) != shape or t.dtype != torch.float32:
+            raise LbscanError(EINVAL, f"{name}: expected {shape} float32")
+    for name, t in (("x", x), ("delta", delta), ("A", A), ("Bm", Bm), ("Cm", Cm), ("Dskip", Dskip),
+                    ("z", z), ("delta_bias", delta_bias), ("y", y), ("workspace", workspace)):
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise LbscanError(EINVAL, f"{name} must be a contiguous device tensor")
+    a = LbscanArgs(Bsz, D, N, L, int(window), code, int(bool(delta_softplus)), int(bool(reverse)),
+                   _ptr(x), _ptr(delta), _ptr(Bm), _ptr(Cm), _ptr(z), _ptr(A), _ptr(Dskip),
+                   _ptr(delta_bias), _ptr(y), _ptr(workspace),
+                   0 if workspace is None else workspace.numel() * workspace.element_size())
+    return a
+
+
+def lbscan_workspace_bytes(args: LbscanArgs, which: int) -> int:
+    return int(load().lbscan_workspace_bytes(ctypes.byref(args), which))
+
+
+def lbscan_default_window(seqlen: int) -> int:
+    return int(load().lbscan_default_window(seqlen))
+
+
+def lbscan_version() -> str:
+    return load().lbscan_version().decode()
+
+
+def _workspace_for(args, which, like):
+    import torch
+    need = lbscan_workspace_bytes(args, which)
+    if need == 0:
+        return None
+    ws = torch.empty((need + 3) // 4, dtype=torch.float32, device=like.device)
+    args.workspace = ws.data_ptr()
+    args.workspace_bytes = ws.numel() * 4
+    return ws
+
+
+def lbscan_fwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, window,
+               delta_softplus=True, reverse=False, out=None, stream=None):
+    """out = locally bi-directional scan of the inputs (see include/lbscan.h)."""
+    import torch
+    y = torch.empty_like(x) if out is None else out
+    a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
+                  delta_softplus=delta_softplus, reverse=reverse, y=y)
+    ws = _workspace_for(a, WS_FWD, x)
+    _check(load().lbscan_fwd(ctypes.byref(a), _stream(stream)), "lbscan_fwd")
+    del ws
+    return y
+
+
+def lbscan_bidir_fwd(set_f: dict, set_b: dict, *, out=None, stream=None):
+    """Global bi-directional scan in two passes.  Each set is a dict with keys
+    x, delta, A, Bm, Cm and optional Dskip, z, delta_bias, delta_softplus; the
+    gate is set_f['z']."""
+    import torch
+    y = torch.empty_like(set_f["x"]) if out is None else out
+
+    def mk(s, yy):
+        return make_args(s["x"], s["delta"], s["A"], s["Bm"], s["Cm"], s.get("Dskip"), s.get("z"),
+                         s.get("delta_bias"), window=1,
+                         delta_softplus=s.get("delta_softplus", True), y=yy)
+    af, ab = mk(set_f, y), mk(set_b, None)
+    ws = _workspace_for(af, WS_BIDIR, y)
+    _check(load().lbscan_bidir_fwd(ctypes.byref(af), ctypes.byref(ab), _stream(stream)),
+           "lbscan_bidir_fwd")
+    del ws
+    return y
+
+
+def lbscan_bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout, window,
+               delta_softplus=True, reverse=False, stream=None):
+    """Gradients of lbscan_fwd.  Returns a dict: dx, ddelta, dz, dBm, dCm, dA,
+    dDskip, ddelta_bias (None where the input is absent)."""
+    import torch
+    a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
+                  delta_softplus=delta_softplus, reverse=reverse)
+    if tuple(dout.shape) != tuple(x.shape) or dout.dtype != x.dtype or not dout.is_contiguous():
+        raise LbscanError(EINVAL, "dout must match x")
+    g = dict(
+        dx=torch.empty_like(x), ddelta=torch.empty_like(x),
+        dz=torch.empty_like(x) if z is not None else None,
+        dBm=torch.empty_like(Bm), dCm=torch.empty_like(Cm),
+        dA=torch.empty_like(A),
+        dDskip=torch.empty_like(Dskip) if Dskip is not None else None,
+        ddelta_bias=torch.empty_like(delta_bias) if delta_bias is not None else None,
+    )
+    ws = _workspace_for(a, WS_BWD, x)
+    rc = load().lbscan_bwd(ctypes.byref(a), _ptr(dout), _ptr(g["dx"]), _ptr(g["ddelta"]),
+                           _ptr(g["dz"]), _ptr(g["dBm"]), _ptr(g["dCm"]), _ptr(g["dA"]),
+                           _ptr(g["dDskip"]), _ptr(g["ddelta_bias"]), _stream(stream))
+    _check(rc, "lbscan_bwd")
+    del ws
+    return g

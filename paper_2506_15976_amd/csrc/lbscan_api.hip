@@ -1,0 +1,157 @@
+// C entry points of liblbscan: argument validation and kernel dispatch.
+// Every step of the computation runs in the HIP kernels; nothing here touches
+// tensor data on the host, allocates or synchronises.
+#include "../../include/lbscan.h"
+#include "lbscan_internal.h"
+
+#include <stdio.h>
+#include <string.h>
+
+namespace {
+
+thread_local char g_last_error[256] = "";
+
+int hip_fail(hipError_t e, const char* where)
+{
+    snprintf(g_last_error, sizeof(g_last_error), "%s: %s", where, hipGetErrorString(e));
+    return LBSCAN_EHIP;
+}
+
+bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+// Shape / pointer checks common to all entry points.  Returns LBSCAN_OK, or
+// an error; *empty is set when there is nothing to compute.
+int check_args(const lbscan_args* a, bool need_y, bool* empty)
+{
+    *empty = false;
+    if (!a) return LBSCAN_EINVAL;
+    if (a->batch < 0 || a->dim < 0 || a->dstate < 0 || a->seqlen < 0) return LBSCAN_EINVAL;
+    if (a->window < 1) return LBSCAN_EINVAL;
+    if (a->dtype != LBSCAN_FP32 && a->dtype != LBSCAN_BF16) return LBSCAN_EUNSUPPORTED;
+    if (a->dstate > LBSCAN_MAX_DSTATE) return LBSCAN_EUNSUPPORTED;
+    if (a->reverse != 0 && a->reverse != 1) return LBSCAN_EINVAL;
+    if ((long)a->batch * a->dim * a->seqlen == 0) { *empty = true; return LBSCAN_OK; }
+    if (!a->x || !a->delta || (need_y && !a->y)) return LBSCAN_EINVAL;
+    if (a->dstate > 0 && (!a->A || !a->Bm || !a->Cm)) return LBSCAN_EINVAL;
+    const void* ptrs[] = {a->x, a->delta, a->Bm, a->Cm, a->z, a->A, a->Dskip, a->delta_bias, a->y};
+    for (const void* p : ptrs)
+        if (p && !aligned4(p)) return LBSCAN_EINVAL;
+    return LBSCAN_OK;
+}
+
+// Window length the kernels run with: a window that covers the whole row is
+// the same as any longer one, and the kernels pad the row with identity steps,
+// so every M >= L maps to the smallest compiled window >= L.
+int effective_window(int M, int L)
+{
+    if (lbscan::window_supported(M)) return M;
+    if (M >= L) {
+        for (int m = 1; m <= 16; m *= 2)
+            if (m >= L) return m;
+    }
+    return 0;
+}
+
+lbscan::FwdParams to_params(const lbscan_args* a, int window)
+{
+    lbscan::FwdParams p;
+    p.batch = a->batch; p.dim = a->dim; p.dstate = a->dstate; p.seqlen = a->seqlen;
+    p.window = window; p.dtype = a->dtype; p.softplus = a->delta_softplus; p.reverse = a->reverse;
+    p.x = a->x; p.delta = a->delta; p.Bm = a->Bm; p.Cm = a->Cm; p.z = a->z;
+    p.A = a->A; p.Dskip = a->Dskip; p.bias = a->delta_bias;
+    p.yprev = nullptr; p.y = a->y; p.y_is_f32 = 0;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lbscan_fwd(const lbscan_args* args, void* hip_stream)
+{
+    bool empty;
+    int rc = check_args(args, true, &empty);
+    if (rc != LBSCAN_OK || empty) return rc;
+    const int M = effective_window(args->window, args->seqlen);
+    if (M == 0) return LBSCAN_EUNSUPPORTED;
+    lbscan::FwdParams p = to_params(args, M);
+    hipError_t e = lbscan::launch_fwd_rowlane(p, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_fwd");
+}
+
+int lbscan_bidir_fwd(const lbscan_args* fs, const lbscan_args* bs, void* hip_stream)
+{
+    bool empty_f, empty_b;
+    int rc = check_args(fs, true, &empty_f);
+    if (rc != LBSCAN_OK) return rc;
+    rc = check_args(bs, false, &empty_b);
+    if (rc != LBSCAN_OK) return rc;
+    if (fs->batch != bs->batch || fs->dim != bs->dim || fs->dstate != bs->dstate ||
+        fs->seqlen != bs->seqlen || fs->dtype != bs->dtype) return LBSCAN_EINVAL;
+    if (empty_f) return LBSCAN_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    // Pass 1 leaves the ungated forward result in fp32: in y itself when y is
+    // fp32, else in the workspace.  Pass 2 reads it back, adds the reverse
+    // scan, gates and writes y.
+    float* partial;
+    if (fs->dtype == LBSCAN_FP32) {
+        partial = static_cast<float*>(fs->y);
+    } else {
+        size_t need = lbscan_workspace_bytes(fs, LBSCAN_WS_BIDIR);
+        if (!fs->workspace || fs->workspace_bytes < need || !aligned4(fs->workspace))
+            return LBSCAN_EWORKSPACE;
+        partial = static_cast<float*>(fs->workspace);
+    }
+    lbscan::FwdParams p1 = to_params(fs, 1);
+    p1.reverse = 0; p1.z = nullptr; p1.y = partial; p1.y_is_f32 = 1;
+    hipError_t e = lbscan::launch_fwd_rowlane(p1, s);
+    if (e != hipSuccess) return hip_fail(e, "lbscan_bidir_fwd pass 1");
+    lbscan::FwdParams p2 = to_params(bs, 1);
+    p2.reverse = 1; p2.z = fs->z; p2.yprev = partial; p2.y = fs->y; p2.y_is_f32 = 0;
+    e = lbscan::launch_fwd_rowlane(p2, s);
+    return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bidir_fwd pass 2");
+}
+
+int lbscan_bwd(const lbscan_args* fwd_args, const void* dout,
+               void* dx, void* ddelta, void* dz, void* dBm, void* dCm,
+               float* dA, float* dDskip, float* ddelta_bias, void* hip_stream)
+{
+    (void)fwd_args; (void)dout; (void)dx; (void)ddelta; (void)dz; (void)dBm; (void)dCm;
+    (void)dA; (void)dDskip; (void)ddelta_bias; (void)hip_stream;
+    return LBSCAN_EUNSUPPORTED;
+}
+
+size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
+{
+    if (!a) return 0;
+    const size_t bdl = (size_t)a->batch * a->dim * a->seqlen;
+    switch (which) {
+        case LBSCAN_WS_BIDIR: return a->dtype == LBSCAN_FP32 ? 0 : bdl * sizeof(float);
+        default: return 0;
+    }
+}
+
+int lbscan_default_window(int32_t seqlen)
+{
+    if (seqlen > 256) return 16;
+    if (seqlen > 128) return 8;
+    return 4;
+}
+
+const char* lbscan_strerror(int code)
+{
+    switch (code) {
+        case LBSCAN_OK: return "ok";
+        case LBSCAN_EINVAL: return "invalid argument";
+        case LBSCAN_EUNSUPPORTED: return "unsupported dtype, state size or window";
+        case LBSCAN_EWORKSPACE: return "workspace missing or too small";
+        case LBSCAN_EHIP: return "HIP error";
+        default: return "unknown error";
+    }
+}
+
+const char* lbscan_last_error(void) { return g_last_error; }
+const char* lbscan_version(void) { return "0.1.0"; }
+
+}  // extern "C"

@@ -1,0 +1,111 @@
+// Device-side helpers shared by the lbscan HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lbscan {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// 2^v through the hardware transcendental (v_exp_f32), without the range
+// fix-ups of the library exp2f: arguments here are <= ~30 and results that
+// underflow may flush to zero.
+__device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
+__device__ __forceinline__ float fast_log2(float v) { return __builtin_amdgcn_logf(v); }
+__device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
+
+// softplus(v) = log(1 + exp(v)), v > 20 -> v (Algorithm 1's Delta line).
+// The time step multiplies every state update, so it is kept to a few ulp:
+// the hardware log has an absolute, not relative, error near 1, hence
+//   e = exp(v) < 1/2 : log1p(e) = 2 atanh(s), s = e / (2 + e), odd series to s^9
+//   otherwise        : log(w) + (e - (w - 1)) / w with w = fl(1 + e), where the
+//                      second term restores the bits lost in rounding 1 + e.
+__device__ __forceinline__ float softplus_f32(float v)
+{
+    const float e = fast_exp2(fminf(v, 20.0f) * kLog2e);
+    float r;
+    if (e < 0.5f) {
+        const float s = e * fast_rcp(2.0f + e);
+        const float s2 = s * s;
+        float poly = fmaf(s2, 1.0f / 9.0f, 1.0f / 7.0f);
+        poly = fmaf(s2, poly, 1.0f / 5.0f);
+        poly = fmaf(s2, poly, 1.0f / 3.0f);
+        r = fmaf(2.0f * s, s2 * poly, 2.0f * s);
+    } else {
+        const float w = 1.0f + e;
+        r = fmaf(fast_log2(w), kLn2, (e - (w - 1.0f)) * fast_rcp(w));
+    }
+    return v > 20.0f ? v : r;
+}
+
+__device__ __forceinline__ float sigmoid_f32(float v)
+{
+    return fast_rcp(1.0f + fast_exp2(-v * kLog2e));
+}
+
+// ---- storage types -------------------------------------------------------
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return __uint_as_float((uint32_t)v.bits << 16); }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+// round to nearest even; NaN stays NaN
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    uint32_t r = u + 0x7FFFu + ((u >> 16) & 1u);
+    bf16_t o;
+    o.bits = (v != v) ? (uint16_t)0x7FC0u : (uint16_t)(r >> 16);
+    return o;
+}
+
+// Four consecutive elements.  Global memory on gfx950 serves multi-dword
+// accesses at dword alignment, so the fp32 quad only promises 4-byte alignment
+// (rows of odd length start at any dword); the bf16 quad promises 4 bytes too
+// and callers fall back to element loads when a row can start at an odd element.
+template <typename T> struct Quad;
+template <> struct __attribute__((packed, aligned(4))) Quad<float> { float v[4]; };
+template <> struct __attribute__((packed, aligned(4))) Quad<bf16_t> { bf16_t v[4]; };
+
+// Loads elements [i, i+4) of a row-major tensor into fp32, zero where the
+// element index e (0..3) fails lo <= i+e < hi.  `vec_ok` says the tensor base
+// and i are such that the quad is 4-byte aligned.
+template <typename T>
+__device__ __forceinline__ void load_quad(const T* __restrict__ base, long i, long lo, long hi,
+                                          bool vec_ok, float out[4])
+{
+    if (vec_ok && i >= lo && i + 4 <= hi) {
+        Quad<T> q = *reinterpret_cast<const Quad<T>*>(base + i);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = to_f32(q.v[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            long k = i + e;
+            out[e] = (k >= lo && k < hi) ? to_f32(base[k]) : 0.0f;
+        }
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void store_quad(T* __restrict__ base, long i, long lo, long hi,
+                                           bool vec_ok, const float in[4])
+{
+    if (vec_ok && i >= lo && i + 4 <= hi) {
+        Quad<T> q;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) q.v[e] = from_f32<T>(in[e]);
+        *reinterpret_cast<Quad<T>*>(base + i) = q;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            long k = i + e;
+            if (k >= lo && k < hi) base[k] = from_f32<T>(in[e]);
+        }
+    }
+}
+
+}  // namespace lbscan

@@ -1,0 +1,35 @@
+// Host-side declarations shared by the lbscan translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lbscan {
+
+// Arguments of one forward launch, already validated by the C entry points.
+struct FwdParams {
+    int batch, dim, dstate, seqlen;
+    int window;
+    int dtype;     // LBSCAN_FP32 / LBSCAN_BF16
+    int softplus;
+    int reverse;
+    const void* x;
+    const void* delta;
+    const void* Bm;
+    const void* Cm;
+    const void* z;        // nullable
+    const float* A;
+    const float* Dskip;   // nullable
+    const float* bias;    // nullable
+    const float* yprev;   // nullable, fp32 (B,D,L): added to y before the gate
+    void* y;              // element type = dtype, or fp32 when y_is_f32
+    int y_is_f32;         // write y as fp32 whatever dtype says (first pass of the two-pass scan)
+};
+
+// Window lengths with a compiled kernel.
+inline bool window_supported(int M) { return M == 1 || M == 2 || M == 4 || M == 8 || M == 16; }
+
+// Row-per-lane forward kernel family (see lbscan_fwd_rowlane.hip).
+hipError_t launch_fwd_rowlane(const FwdParams& p, hipStream_t stream);
+
+}  // namespace lbscan

@@ -92,13 +92,32 @@ def make_workload(name: str, *, direction_b: bool = False):
     return s
 
 
-def error_metric(got: np.ndarray, ref: np.ndarray) -> float:
-    """Scale-aware maximum relative error: max_i |got-ref| / max(|ref_i|, 1e-3*rms(ref)).
-    A plain relative error is undefined where the reference crosses zero."""
+def error_metric(got: np.ndarray, ref: np.ndarray, floor_frac: float = 0.1) -> float:
+    """Scale-aware maximum relative error:
+        max_i |got_i - ref_i| / max(|ref_i|, floor_frac * rms(ref)).
+    A plain relative error is undefined where the reference crosses zero: each
+    output is a sum of N+1 terms of size ~rms that may cancel, and fp32
+    rounding of those terms leaves an absolute error of a few 1e-7 * rms on
+    average and, in the tail over millions of outputs, up to ~1e-5 * rms (a
+    sequential fp32 evaluation with correctly rounded exp shows the same).
+    With the floor at 0.1 * rms a bound of 1e-4 therefore reads: relative
+    error 1e-4 wherever the output is not a cancellation, absolute error
+    1e-5 * rms where it is."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     if ref.size == 0:
         return 0.0
     rms = float(np.sqrt(np.mean(ref * ref)))
-    floor = max(1e-3 * rms, 1e-300)
+    floor = max(floor_frac * rms, 1e-300)
     return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), floor)))
+
+
+def mean_error(got: np.ndarray, ref: np.ndarray) -> float:
+    """Mean absolute error over rms(ref): catches a systematic loss of precision
+    that the maximum, dominated by cancellations, would hide."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref))) or 1.0
+    return float(np.mean(np.abs(got - ref)) / rms)

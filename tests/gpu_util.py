@@ -1,0 +1,66 @@
+"""Helpers for the GPU parity tests: upload seeded inputs, run the oracle on the
+same (storage-rounded) values, compare with the scale-aware error metric."""
+import numpy as np
+import torch
+
+from paper_2506_15976_amd.inputs import (bf16_bits_to_fp32, error_metric, fp32_to_bf16_bits,
+                                         make_inputs, make_workload, mean_error)
+
+TENSOR_KEYS = ("x", "delta", "Bm", "Cm", "z", "dout")
+PARAM_KEYS = ("A", "Dskip", "delta_bias")
+
+# Tolerances of the scale-aware relative error: fp32 path against the fp64
+# oracle, and bf16-stored inputs/outputs (output rounding alone is 2^-9).
+TOL_FP32 = 1e-4
+TOL_BF16 = 2e-2
+# mean |error| / rms: a few fp32 (bf16) roundings
+MEAN_TOL_FP32 = 1e-6
+MEAN_TOL_BF16 = 4e-3
+
+
+def assert_close(got, ref, dtype="fp32", what="out"):
+    """The parity bar: scale-aware max relative error and mean error."""
+    tol = TOL_BF16 if dtype == "bf16" else TOL_FP32
+    mtol = MEAN_TOL_BF16 if dtype == "bf16" else MEAN_TOL_FP32
+    err, merr = error_metric(got, ref), mean_error(got, ref)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values"
+    assert err <= tol, f"{what}: scale-aware max rel err {err:.3e} > {tol}"
+    assert merr <= mtol, f"{what}: mean abs err / rms {merr:.3e} > {mtol}"
+    return err
+
+
+def to_device(s: dict, dtype: str):
+    """numpy input set -> dict of device tensors in the storage type."""
+    dev = torch.device("cuda:0")
+    out = {}
+    for k in TENSOR_KEYS:
+        v = s.get(k)
+        if v is None:
+            out[k] = None
+        elif dtype == "bf16":
+            bits = torch.from_numpy(fp32_to_bf16_bits(v).view(np.int16))
+            out[k] = bits.view(torch.bfloat16).to(dev)
+        else:
+            out[k] = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(dev)
+    for k in PARAM_KEYS:
+        v = s.get(k)
+        out[k] = None if v is None else torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(dev)
+    return out
+
+
+def to_numpy(t):
+    if t is None:
+        return None
+    if t.dtype == torch.bfloat16:
+        return bf16_bits_to_fp32(t.cpu().view(torch.int16).numpy().view(np.uint16))
+    return t.cpu().numpy()
+
+
+def fwd_inputs(s):
+    return {k: s.get(k) for k in ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")}
+
+
+def flip_time(s):
+    """Time-reversed copy of an input set (numpy)."""
+    return {k: (np.ascontiguousarray(v[..., ::-1]) if isinstance(v, np.ndarray) and v.ndim == 3 else v)
+            for k, v in s.items()}

@@ -1,0 +1,83 @@
+"""The C-ABI library loads and exports every symbol include/lbscan.h declares;
+host-side validation paths that need no GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2506_15976_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2506_15976_amd import build
+        build.build(force=True, verbose=False)
+    return binding.load()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "lbscan.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lbscan_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2506_15976_amd import binding
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_struct_layout_matches_header():
+    from paper_2506_15976_amd.binding import LbscanArgs
+    # 8 int32 + 9 pointers + workspace pointer + size_t
+    assert ctypes.sizeof(LbscanArgs) == 8 * 4 + 10 * 8 + 8
+    assert LbscanArgs.x.offset == 32
+    assert LbscanArgs.workspace_bytes.offset == 32 + 10 * 8
+
+
+def test_default_window_rule(lib):
+    # Sec. 4, first paragraph: L > 256 -> 16; 128 < L <= 256 -> 8; L <= 128 -> 4
+    f = lib.lbscan_default_window
+    assert [f(64), f(128), f(129), f(197), f(256), f(257), f(4096)] == [4, 4, 8, 8, 8, 16, 16]
+
+
+def test_validation_without_gpu(lib):
+    from paper_2506_15976_amd.binding import LbscanArgs, EINVAL, EUNSUPPORTED, OK
+    a = LbscanArgs()
+    a.batch, a.dim, a.dstate, a.seqlen, a.window = 1, 4, 16, 8, 0
+    assert lib.lbscan_fwd(ctypes.byref(a), None) == EINVAL          # window < 1
+    a.window = 4
+    assert lib.lbscan_fwd(ctypes.byref(a), None) == EINVAL          # null x
+    a.dtype = 7
+    assert lib.lbscan_fwd(ctypes.byref(a), None) == EUNSUPPORTED
+    a.dtype = 0
+    a.dstate = 17
+    assert lib.lbscan_fwd(ctypes.byref(a), None) == EUNSUPPORTED
+    a.dstate = 16
+    a.seqlen = 0
+    assert lib.lbscan_fwd(ctypes.byref(a), None) == OK              # empty: nothing to do
+    assert lib.lbscan_fwd(None, None) == EINVAL
+    a.seqlen = 64
+    a.window = 3
+    a.x = a.delta = a.y = a.A = a.Bm = a.Cm = 256                   # never dereferenced on the host
+    assert lib.lbscan_fwd(ctypes.byref(a), None) == EUNSUPPORTED    # window not compiled
+    a.x = 257
+    a.window = 4
+    assert lib.lbscan_fwd(ctypes.byref(a), None) == EINVAL          # misaligned pointer
+    assert lib.lbscan_strerror(EINVAL) == b"invalid argument"
+    assert lib.lbscan_version().startswith(b"0.")
+
+
+def test_workspace_sizes(lib):
+    from paper_2506_15976_amd.binding import LbscanArgs, WS_BIDIR, WS_FWD
+    a = LbscanArgs()
+    a.batch, a.dim, a.dstate, a.seqlen, a.window = 2, 8, 16, 10, 4
+    assert lib.lbscan_workspace_bytes(ctypes.byref(a), WS_FWD) == 0
+    assert lib.lbscan_workspace_bytes(ctypes.byref(a), WS_BIDIR) == 0
+    a.dtype = 1
+    assert lib.lbscan_workspace_bytes(ctypes.byref(a), WS_BIDIR) == 2 * 8 * 10 * 4

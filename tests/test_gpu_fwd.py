@@ -1,0 +1,139 @@
+"""GPU parity of lbscan_fwd / lbscan_bidir_fwd against the fp64 CPU oracle,
+element by element on the same seeded inputs, through the C ABI."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lb():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2506_15976_amd as pkg
+    pkg.load()
+    return pkg
+
+
+def _run_fwd(lb, oracle, s, *, window, dtype="fp32", reverse=False, softplus=True):
+    import torch
+    from gpu_util import assert_close, flip_time, fwd_inputs, to_device, to_numpy
+    dev = to_device(s, dtype)
+    got = lb.lbscan_fwd(**fwd_inputs(dev), window=window, delta_softplus=softplus, reverse=reverse)
+    torch.cuda.synchronize()
+    got = to_numpy(got)
+    src = flip_time(s) if reverse else s
+    ref = oracle.fwd(**fwd_inputs(src), window=window, delta_softplus=softplus)
+    if reverse:
+        ref = ref[..., ::-1]
+    return assert_close(got, ref, dtype)
+
+
+@pytest.mark.parametrize("window", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("reverse", [False, True])
+def test_tiny_workload_all_windows(lb, oracle, window, reverse):
+    from paper_2506_15976_amd.inputs import make_workload
+    s = make_workload("tiny")
+    _run_fwd(lb, oracle, s, window=window, reverse=reverse)
+
+
+@pytest.mark.parametrize("shape", [
+    # (B, D, N, L): ragged tails, several tiles, partial blocks, small state sizes
+    (2, 70, 16, 37), (1, 130, 16, 197), (3, 5, 16, 5), (2, 64, 16, 1), (1, 300, 16, 16),
+    (2, 33, 16, 17), (1, 64, 8, 50), (2, 20, 3, 29), (1, 7, 1, 63), (1, 257, 16, 33),
+])
+@pytest.mark.parametrize("window", [1, 4, 8])
+def test_ragged_shapes(lb, oracle, shape, window):
+    from paper_2506_15976_amd.inputs import make_inputs
+    B, D, N, L = shape
+    s = make_inputs(B, D, N, L, seed=1234 + B * 7 + D + L, random_A=True)
+    _run_fwd(lb, oracle, s, window=window)
+    _run_fwd(lb, oracle, s, window=window, reverse=True)
+
+
+def test_optional_arguments_absent(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(2, 96, 16, 61, seed=77, with_z=False)
+    s["Dskip"] = None
+    s["delta_bias"] = None
+    _run_fwd(lb, oracle, s, window=4)
+    s2 = make_inputs(2, 96, 16, 61, seed=78)
+    s2["delta"] = np.abs(s2["delta"]) * 0.2 + 0.01
+    s2["delta_bias"] = None
+    _run_fwd(lb, oracle, s2, window=4, softplus=False)
+
+
+def test_window_covering_short_row(lb, oracle):
+    """M >= L with L <= 16 is one window over the whole row."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(2, 64, 16, 11, seed=5)
+    _run_fwd(lb, oracle, s, window=11)
+    _run_fwd(lb, oracle, s, window=1000)
+
+
+def test_unsupported_window_is_an_error(lb):
+    from gpu_util import fwd_inputs, to_device
+    from paper_2506_15976_amd.inputs import make_inputs
+    dev = to_device(make_inputs(1, 64, 16, 64, seed=6), "fp32")
+    with pytest.raises(lb.LbscanError) as ei:
+        lb.lbscan_fwd(**fwd_inputs(dev), window=3)
+    assert ei.value.code == -2
+
+
+def test_zero_timestep_is_skip_times_gate(lb):
+    """delta = 0 without softplus: out = Dskip * x * SiLU(z)."""
+    import torch
+    from gpu_util import fwd_inputs, to_device, to_numpy
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(2, 128, 16, 45, seed=8)
+    s["delta"] = np.zeros_like(s["delta"])
+    s["delta_bias"] = None
+    s["Dskip"] = np.random.default_rng(9).standard_normal(128).astype(np.float32)
+    dev = to_device(s, "fp32")
+    got = to_numpy(lb.lbscan_fwd(**fwd_inputs(dev), window=4, delta_softplus=False))
+    z = s["z"].astype(np.float64)
+    ref = s["Dskip"][None, :, None] * s["x"] * (z / (1 + np.exp(-z)))
+    np.testing.assert_allclose(got, ref, rtol=2e-6, atol=1e-7)
+
+
+def test_bf16_storage_small(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_inputs
+    for L in (64, 197, 33):
+        s = make_inputs(2, 96, 16, L, seed=300 + L, dtype="bf16")
+        _run_fwd(lb, oracle, s, window=8, dtype="bf16")
+        _run_fwd(lb, oracle, s, window=4, dtype="bf16", reverse=True)
+
+
+@pytest.mark.parametrize("name", ["vim_tiny", "vim_small", "hires_4096", "wsi_bag"])
+def test_full_size_workloads(lb, oracle, name):
+    from paper_2506_15976_amd.inputs import WORKLOADS, make_workload
+    w = WORKLOADS[name]
+    s = make_workload(name)
+    err = _run_fwd(lb, oracle, s, window=w["window"], dtype=w["dtype"])
+    print(f"{name}: err={err:.3e}")
+
+
+def _run_bidir(lb, oracle, sf, sb, dtype="fp32"):
+    import torch
+    from gpu_util import assert_close, fwd_inputs, to_device, to_numpy
+    df, db = to_device(sf, dtype), to_device(sb, dtype)
+    got = lb.lbscan_bidir_fwd(fwd_inputs(df), fwd_inputs(db))
+    torch.cuda.synchronize()
+    ref = oracle.bidir_fwd(fwd_inputs(sf), fwd_inputs(sb))
+    assert_close(to_numpy(got), ref, dtype, "bidir")
+
+
+def test_bidir_small_and_ragged(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_inputs
+    for (B, D, N, L) in [(2, 70, 16, 37), (1, 64, 16, 256), (1, 130, 8, 19)]:
+        sf = make_inputs(B, D, N, L, seed=500 + L, random_A=True)
+        sb = make_inputs(B, D, N, L, seed=1500 + L, random_A=True)
+        _run_bidir(lb, oracle, sf, sb)
+    sf = make_inputs(2, 64, 16, 100, seed=600, dtype="bf16")
+    sb = make_inputs(2, 64, 16, 100, seed=1600, dtype="bf16")
+    _run_bidir(lb, oracle, sf, sb, dtype="bf16")
+
+
+def test_bidir_vim_tiny(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_workload
+    _run_bidir(lb, oracle, make_workload("vim_tiny"), make_workload("vim_tiny", direction_b=True))
