@@ -27,8 +27,8 @@
  * Ownership: every data pointer is a caller-owned DEVICE pointer.  The library
  * never allocates, frees or synchronises; it enqueues work on the HIP stream
  * passed in (a hipStream_t cast to void*, NULL = default stream) and returns.
- * Outputs are fully overwritten.  Calls are re-entrant; there is no global
- * state besides a thread-local last-error string.
+ * Outputs are fully overwritten.  Calls are re-entrant; the only global state
+ * is a thread-local last-error string and the options of lbscan_set_option.
  *
  * Errors: 0 on success, a negative LBSCAN_E* code otherwise; nothing is
  * enqueued when an error is returned before launch.
@@ -112,6 +112,14 @@ size_t lbscan_workspace_bytes(const lbscan_args *args, int which);
 /* Window length the paper uses for a sequence length (Sec. 4, first paragraph):
  * L > 256 -> 16, 128 < L <= 256 -> 8, otherwise 4. */
 int lbscan_default_window(int32_t seqlen);
+
+/* Process-wide launch-shape override, for tuning and for tests that must reach
+ * every kernel variant; results do not depend on it beyond rounding order.
+ *   "waves_log2": -1 (default) lets the library choose over how many waves of
+ *                 a block the N states of a row are split; 0..3 forces 1, 2, 4
+ *                 or 8 (clamped to what the state size allows).
+ * Returns LBSCAN_EINVAL for an unknown name or a value out of range. */
+int lbscan_set_option(const char *name, int value);
 
 const char *lbscan_strerror(int code);
 /* Text of the last HIP error seen by this thread ("" if none). */

@@ -20,6 +20,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 EXPORTS = (
     "lbscan_fwd", "lbscan_bwd", "lbscan_bidir_fwd", "lbscan_workspace_bytes",
     "lbscan_default_window", "lbscan_strerror", "lbscan_last_error", "lbscan_version",
+    "lbscan_set_option",
 )
 
 
@@ -69,6 +70,8 @@ def load():
     lib.lbscan_workspace_bytes.argtypes = [ap, ctypes.c_int]
     lib.lbscan_default_window.restype = ctypes.c_int
     lib.lbscan_default_window.argtypes = [ctypes.c_int32]
+    lib.lbscan_set_option.restype = ctypes.c_int
+    lib.lbscan_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
     lib.lbscan_strerror.restype = ctypes.c_char_p
     lib.lbscan_strerror.argtypes = [ctypes.c_int]
     lib.lbscan_last_error.restype = ctypes.c_char_p
@@ -141,6 +144,10 @@ def lbscan_workspace_bytes(args: LbscanArgs, which: int) -> int:
 
 def lbscan_default_window(seqlen: int) -> int:
     return int(load().lbscan_default_window(seqlen))
+
+
+def lbscan_set_option(name: str, value: int) -> None:
+    _check(load().lbscan_set_option(name.encode(), int(value)), "lbscan_set_option")
 
 
 def lbscan_version() -> str:

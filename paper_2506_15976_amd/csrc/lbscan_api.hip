@@ -4,7 +4,9 @@
 #include "../../include/lbscan.h"
 #include "lbscan_internal.h"
 
+#include <atomic>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 namespace {
@@ -16,6 +18,10 @@ int hip_fail(hipError_t e, const char* where)
     snprintf(g_last_error, sizeof(g_last_error), "%s: %s", where, hipGetErrorString(e));
     return LBSCAN_EHIP;
 }
+
+// Launch-shape overrides set through lbscan_set_option (tuning and tests).
+std::atomic<int> g_waves_log2{-1};
+int tuning_waves_log2() { return g_waves_log2.load(std::memory_order_relaxed); }
 
 bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
@@ -30,6 +36,7 @@ int check_args(const lbscan_args* a, bool need_y, bool* empty)
     if (a->dtype != LBSCAN_FP32 && a->dtype != LBSCAN_BF16) return LBSCAN_EUNSUPPORTED;
     if (a->dstate > LBSCAN_MAX_DSTATE) return LBSCAN_EUNSUPPORTED;
     if (a->reverse != 0 && a->reverse != 1) return LBSCAN_EINVAL;
+    if (a->seqlen > (1 << 24)) return LBSCAN_EUNSUPPORTED;   // 64 rows * L is indexed in 32 bits
     if ((long)a->batch * a->dim * a->seqlen == 0) { *empty = true; return LBSCAN_OK; }
     if (!a->x || !a->delta || (need_y && !a->y)) return LBSCAN_EINVAL;
     if (a->dstate > 0 && (!a->A || !a->Bm || !a->Cm)) return LBSCAN_EINVAL;
@@ -60,6 +67,7 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     p.x = a->x; p.delta = a->delta; p.Bm = a->Bm; p.Cm = a->Cm; p.z = a->z;
     p.A = a->A; p.Dskip = a->Dskip; p.bias = a->delta_bias;
     p.yprev = nullptr; p.y = a->y; p.y_is_f32 = 0;
+    p.force_waves_log2 = tuning_waves_log2();
     return p;
 }
 
@@ -75,7 +83,7 @@ int lbscan_fwd(const lbscan_args* args, void* hip_stream)
     const int M = effective_window(args->window, args->seqlen);
     if (M == 0) return LBSCAN_EUNSUPPORTED;
     lbscan::FwdParams p = to_params(args, M);
-    hipError_t e = lbscan::launch_fwd_rowlane(p, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = lbscan::launch_fwd(p, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_fwd");
 }
 
@@ -105,11 +113,11 @@ int lbscan_bidir_fwd(const lbscan_args* fs, const lbscan_args* bs, void* hip_str
     }
     lbscan::FwdParams p1 = to_params(fs, 1);
     p1.reverse = 0; p1.z = nullptr; p1.y = partial; p1.y_is_f32 = 1;
-    hipError_t e = lbscan::launch_fwd_rowlane(p1, s);
+    hipError_t e = lbscan::launch_fwd(p1, s);
     if (e != hipSuccess) return hip_fail(e, "lbscan_bidir_fwd pass 1");
     lbscan::FwdParams p2 = to_params(bs, 1);
     p2.reverse = 1; p2.z = fs->z; p2.yprev = partial; p2.y = fs->y; p2.y_is_f32 = 0;
-    e = lbscan::launch_fwd_rowlane(p2, s);
+    e = lbscan::launch_fwd(p2, s);
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bidir_fwd pass 2");
 }
 
@@ -149,6 +157,17 @@ const char* lbscan_strerror(int code)
         case LBSCAN_EHIP: return "HIP error";
         default: return "unknown error";
     }
+}
+
+int lbscan_set_option(const char* name, int value)
+{
+    if (!name) return LBSCAN_EINVAL;
+    if (strcmp(name, "waves_log2") == 0) {
+        if (value < -1 || value > 3) return LBSCAN_EINVAL;
+        g_waves_log2.store(value, std::memory_order_relaxed);
+        return LBSCAN_OK;
+    }
+    return LBSCAN_EINVAL;
 }
 
 const char* lbscan_last_error(void) { return g_last_error; }

@@ -24,12 +24,18 @@ struct FwdParams {
     const float* yprev;   // nullable, fp32 (B,D,L): added to y before the gate
     void* y;              // element type = dtype, or fp32 when y_is_f32
     int y_is_f32;         // write y as fp32 whatever dtype says (first pass of the two-pass scan)
+    int force_waves_log2; // >= 0: override the state-split heuristic (tests, tuning)
 };
 
 // Window lengths with a compiled kernel.
 inline bool window_supported(int M) { return M == 1 || M == 2 || M == 4 || M == 8 || M == 16; }
 
-// Row-per-lane forward kernel family (see lbscan_fwd_rowlane.hip).
-hipError_t launch_fwd_rowlane(const FwdParams& p, hipStream_t stream);
+// Row-per-lane forward kernel family (lbscan_fwd_rowlane.inc), one translation
+// unit per storage type.  waves_log2: log2 of the waves the states are split over.
+hipError_t launch_fwd_rowlane_f32(const FwdParams& p, int waves_log2, hipStream_t stream);
+hipError_t launch_fwd_rowlane_bf16(const FwdParams& p, int waves_log2, hipStream_t stream);
+
+// Picks the launch shape for the sizes in p and launches the forward kernel.
+hipError_t launch_fwd(const FwdParams& p, hipStream_t stream);
 
 }  // namespace lbscan

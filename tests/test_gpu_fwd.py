@@ -51,6 +51,22 @@ def test_ragged_shapes(lb, oracle, shape, window):
     _run_fwd(lb, oracle, s, window=window, reverse=True)
 
 
+@pytest.mark.parametrize("waves_log2", [0, 1, 2, 3])
+def test_every_state_split_variant(lb, oracle, waves_log2):
+    """The states of a row can be split over 1, 2, 4 or 8 waves; force each."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    lb.lbscan_set_option("waves_log2", waves_log2)
+    try:
+        for (B, D, N, L, M) in [(2, 70, 16, 37, 4), (1, 130, 8, 50, 8), (1, 64, 5, 33, 2), (2, 64, 16, 197, 16)]:
+            s = make_inputs(B, D, N, L, seed=4000 + D + L, random_A=True)
+            _run_fwd(lb, oracle, s, window=M)
+            _run_fwd(lb, oracle, s, window=M, reverse=True)
+        s = make_inputs(1, 96, 16, 64, seed=4100, dtype="bf16")
+        _run_fwd(lb, oracle, s, window=4, dtype="bf16")
+    finally:
+        lb.lbscan_set_option("waves_log2", -1)
+
+
 def test_optional_arguments_absent(lb, oracle):
     from paper_2506_15976_amd.inputs import make_inputs
     s = make_inputs(2, 96, 16, 61, seed=77, with_z=False)
