@@ -85,6 +85,7 @@ def main():
     ap.add_argument("--shape", default="", help="B,D,N,L,M[,dtype]: time a custom shape instead of a named workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--waves-log2", type=int, default=-1, help="force the state-split launch shape (tuning)")
+    ap.add_argument("--segments", type=int, default=0, help="force the number of row segments (tuning)")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets to rotate over (0: enough for 640 MB)")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -101,6 +102,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     lib = lb.load()
     lb.lbscan_set_option("waves_log2", a.waves_log2)
+    lb.lbscan_set_option("segments", a.segments)
     if a.shape:
         f = a.shape.split(",")
         w = dict(batch=int(f[0]), dim=int(f[1]), dstate=int(f[2]), seqlen=int(f[3]), window=int(f[4]),
@@ -126,6 +128,10 @@ def main():
 
     ys = [torch.empty_like(s["x"]) for s in sets]
     fwd_args = [lb.make_args(**s, window=w["window"], y=y) for s, y in zip(sets, ys)]
+    need = lb.lbscan_workspace_bytes(fwd_args[0], binding.WS_FWD)
+    ws_fwd = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
+    for ar in fwd_args:
+        ar.workspace, ar.workspace_bytes = ws_fwd.data_ptr(), need
     fwd_calls = [(lambda ar=ar: lib.lbscan_fwd(ctypes.byref(ar), stream)) for ar in fwd_args]
     rc = fwd_calls[0]()
     assert rc == 0, f"lbscan_fwd failed: {rc}"
@@ -136,12 +142,10 @@ def main():
     # two-pass global bi-directional scan on the same inputs (direction b = next slot)
     bi_f = [lb.make_args(**s, window=1, y=y) for s, y in zip(sets, ys)]
     bi_b = [lb.make_args(**sets[(i + 1) % nsets], window=1) for i in range(nsets)]
-    ws = None
     need = lb.lbscan_workspace_bytes(bi_f[0], binding.WS_BIDIR)
-    if need:
-        ws = torch.empty(need // 4, dtype=torch.float32, device="cuda:0")
-        for ar in bi_f:
-            ar.workspace, ar.workspace_bytes = ws.data_ptr(), need
+    ws = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
+    for ar in bi_f:
+        ar.workspace, ar.workspace_bytes = ws.data_ptr(), need
     bi_calls = [(lambda f=f, b=b: lib.lbscan_bidir_fwd(ctypes.byref(f), ctypes.byref(b), stream))
                 for f, b in zip(bi_f, bi_b)]
     rc = bi_calls[0]()

@@ -21,13 +21,14 @@ int hip_fail(hipError_t e, const char* where)
 
 // Launch-shape overrides set through lbscan_set_option (tuning and tests).
 std::atomic<int> g_waves_log2{-1};
+std::atomic<int> g_nseg{0};
 int tuning_waves_log2() { return g_waves_log2.load(std::memory_order_relaxed); }
+int tuning_nseg() { return g_nseg.load(std::memory_order_relaxed); }
 
 bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
-// Shape / pointer checks common to all entry points.  Returns LBSCAN_OK, or
-// an error; *empty is set when there is nothing to compute.
-int check_args(const lbscan_args* a, bool need_y, bool* empty)
+// Size and flag checks.  *empty is set when there is nothing to compute.
+int check_args_sizes(const lbscan_args* a, bool* empty)
 {
     *empty = false;
     if (!a) return LBSCAN_EINVAL;
@@ -37,7 +38,15 @@ int check_args(const lbscan_args* a, bool need_y, bool* empty)
     if (a->dstate > LBSCAN_MAX_DSTATE) return LBSCAN_EUNSUPPORTED;
     if (a->reverse != 0 && a->reverse != 1) return LBSCAN_EINVAL;
     if (a->seqlen > (1 << 24)) return LBSCAN_EUNSUPPORTED;   // 64 rows * L is indexed in 32 bits
-    if ((long)a->batch * a->dim * a->seqlen == 0) { *empty = true; return LBSCAN_OK; }
+    if ((long)a->batch * a->dim * a->seqlen == 0) *empty = true;
+    return LBSCAN_OK;
+}
+
+// Shape / pointer checks common to all entry points.
+int check_args(const lbscan_args* a, bool need_y, bool* empty)
+{
+    int rc = check_args_sizes(a, empty);
+    if (rc != LBSCAN_OK || *empty) return rc;
     if (!a->x || !a->delta || (need_y && !a->y)) return LBSCAN_EINVAL;
     if (a->dstate > 0 && (!a->A || !a->Bm || !a->Cm)) return LBSCAN_EINVAL;
     const void* ptrs[] = {a->x, a->delta, a->Bm, a->Cm, a->z, a->A, a->Dskip, a->delta_bias, a->y};
@@ -68,6 +77,8 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     p.A = a->A; p.Dskip = a->Dskip; p.bias = a->delta_bias;
     p.yprev = nullptr; p.y = a->y; p.y_is_f32 = 0;
     p.force_waves_log2 = tuning_waves_log2();
+    p.force_nseg = tuning_nseg();
+    p.nseg = 1; p.seg_tiles = 0; p.summary_only = 0; p.carry = nullptr; p.dsum = nullptr;
     return p;
 }
 
@@ -83,7 +94,10 @@ int lbscan_fwd(const lbscan_args* args, void* hip_stream)
     const int M = effective_window(args->window, args->seqlen);
     if (M == 0) return LBSCAN_EUNSUPPORTED;
     lbscan::FwdParams p = to_params(args, M);
-    hipError_t e = lbscan::launch_fwd(p, static_cast<hipStream_t>(hip_stream));
+    const size_t need = lbscan::fwd_workspace_bytes(p);
+    if (need && (!args->workspace || args->workspace_bytes < need || !aligned4(args->workspace)))
+        return LBSCAN_EWORKSPACE;
+    hipError_t e = lbscan::launch_fwd(p, args->workspace, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_fwd");
 }
 
@@ -100,24 +114,28 @@ int lbscan_bidir_fwd(const lbscan_args* fs, const lbscan_args* bs, void* hip_str
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
     // Pass 1 leaves the ungated forward result in fp32: in y itself when y is
-    // fp32, else in the workspace.  Pass 2 reads it back, adds the reverse
-    // scan, gates and writes y.
+    // fp32, else at the start of the workspace.  Pass 2 reads it back, adds the
+    // reverse scan, gates and writes y.  Both passes share the scratch the
+    // forward kernels need for long rows (they run one after the other).
+    lbscan::FwdParams p1 = to_params(fs, 1);
+    lbscan::FwdParams p2 = to_params(bs, 1);
+    const size_t need = lbscan_workspace_bytes(fs, LBSCAN_WS_BIDIR);
+    if (need && (!fs->workspace || fs->workspace_bytes < need || !aligned4(fs->workspace)))
+        return LBSCAN_EWORKSPACE;
+    const size_t bdl = (size_t)fs->batch * fs->dim * fs->seqlen;
     float* partial;
+    char* scratch = static_cast<char*>(fs->workspace);
     if (fs->dtype == LBSCAN_FP32) {
         partial = static_cast<float*>(fs->y);
     } else {
-        size_t need = lbscan_workspace_bytes(fs, LBSCAN_WS_BIDIR);
-        if (!fs->workspace || fs->workspace_bytes < need || !aligned4(fs->workspace))
-            return LBSCAN_EWORKSPACE;
         partial = static_cast<float*>(fs->workspace);
+        scratch += bdl * sizeof(float);
     }
-    lbscan::FwdParams p1 = to_params(fs, 1);
     p1.reverse = 0; p1.z = nullptr; p1.y = partial; p1.y_is_f32 = 1;
-    hipError_t e = lbscan::launch_fwd(p1, s);
+    hipError_t e = lbscan::launch_fwd(p1, scratch, s);
     if (e != hipSuccess) return hip_fail(e, "lbscan_bidir_fwd pass 1");
-    lbscan::FwdParams p2 = to_params(bs, 1);
     p2.reverse = 1; p2.z = fs->z; p2.yprev = partial; p2.y = fs->y; p2.y_is_f32 = 0;
-    e = lbscan::launch_fwd(p2, s);
+    e = lbscan::launch_fwd(p2, scratch, s);
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bidir_fwd pass 2");
 }
 
@@ -132,10 +150,17 @@ int lbscan_bwd(const lbscan_args* fwd_args, const void* dout,
 
 size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
 {
-    if (!a) return 0;
+    bool empty;
+    if (check_args_sizes(a, &empty) != LBSCAN_OK || empty) return 0;
     const size_t bdl = (size_t)a->batch * a->dim * a->seqlen;
+    int M = effective_window(a->window, a->seqlen);
+    if (M == 0) M = 1;
     switch (which) {
-        case LBSCAN_WS_BIDIR: return a->dtype == LBSCAN_FP32 ? 0 : bdl * sizeof(float);
+        case LBSCAN_WS_FWD:
+            return lbscan::fwd_workspace_bytes(to_params(a, M));
+        case LBSCAN_WS_BIDIR:
+            return (a->dtype == LBSCAN_FP32 ? 0 : bdl * sizeof(float)) +
+                   lbscan::fwd_workspace_bytes(to_params(a, 1));
         default: return 0;
     }
 }
@@ -165,6 +190,11 @@ int lbscan_set_option(const char* name, int value)
     if (strcmp(name, "waves_log2") == 0) {
         if (value < -1 || value > 3) return LBSCAN_EINVAL;
         g_waves_log2.store(value, std::memory_order_relaxed);
+        return LBSCAN_OK;
+    }
+    if (strcmp(name, "segments") == 0) {
+        if (value < 0 || value > (1 << 20)) return LBSCAN_EINVAL;
+        g_nseg.store(value, std::memory_order_relaxed);
         return LBSCAN_OK;
     }
     return LBSCAN_EINVAL;

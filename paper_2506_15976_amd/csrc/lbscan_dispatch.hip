@@ -2,27 +2,85 @@
 #include "lbscan_internal.h"
 
 namespace lbscan {
+namespace {
 
-// The row-per-lane kernel runs one wave per 64 rows and state group.  MI355X
-// has 256 CUs x 4 SIMDs; the scan is bound by VALU issue, which needs a few
-// waves per SIMD to overlap LDS and memory latency.  Split the states over
-// more waves until there are about 4 waves per SIMD (splitting duplicates the
-// per-token work of a row in every wave, so no further than needed).
-static int pick_waves_log2(const FwdParams& p)
+struct Shape { int waves_log2, nseg, seg_tiles; };
+
+// The row-per-lane kernel runs one wave per (64 rows, state group, segment).
+// MI355X has 256 CUs x 4 SIMDs, and the scan is bound by VALU issue, which
+// needs several waves per SIMD to cover LDS and memory latency.
+//  * First split the N states of a row over more waves of the block (this
+//    repeats the per-token work of a row in every wave, so no further than
+//    needed for about 4 waves per SIMD).
+//  * If the rows alone cannot fill the chip even so, cut them into segments
+//    scanned in parallel: a summary launch, the carry chain, then the full
+//    pass started from the carried-in states.  That costs a second read of
+//    x, delta, Bm and ~60% more arithmetic, so only when rows are scarce.
+Shape pick_shape(const FwdParams& p)
 {
-    const long row_blocks = (long)((p.dim + 63) / 64) * p.batch;
+    const long nrb = (long)((p.dim + 63) / 64) * p.batch;
     const int max_log2 = p.dstate > 8 ? 3 : (p.dstate > 4 ? 2 : (p.dstate > 2 ? 1 : 0));
-    if (p.force_waves_log2 >= 0) return p.force_waves_log2 < max_log2 ? p.force_waves_log2 : max_log2;
-    int w = 0;
-    while (w < max_log2 && (row_blocks << w) < 4096) ++w;
-    return w;
+    const int ntiles = (p.seqlen + kTileTokens - 1) / kTileTokens;
+    Shape s{0, 1, ntiles};
+    while (s.waves_log2 < max_log2 && (nrb << s.waves_log2) < 4096) ++s.waves_log2;
+    long want_seg = 1;
+    if ((nrb << max_log2) < 2048) {
+        const int wl = max_log2 < 2 ? max_log2 : 2;
+        s.waves_log2 = wl;
+        want_seg = (6144 + (nrb << wl) - 1) / (nrb << wl);
+    }
+    if (p.force_waves_log2 >= 0) s.waves_log2 = p.force_waves_log2 < max_log2 ? p.force_waves_log2 : max_log2;
+    if (p.force_nseg >= 1) want_seg = p.force_nseg;
+    if (want_seg > 1) {
+        int st = (int)((ntiles + want_seg - 1) / want_seg);
+        if (p.force_nseg < 1 && st < 4) st = 4;               // at least 64 tokens per segment
+        if (st < 1) st = 1;
+        s.seg_tiles = st;
+        s.nseg = (ntiles + st - 1) / st;
+    }
+    return s;
 }
 
-hipError_t launch_fwd(const FwdParams& p, hipStream_t stream)
+size_t carry_floats(const FwdParams& p, int nseg)
+{
+    return (size_t)nseg * p.batch * p.dim * (size_t)p.dstate;
+}
+
+}  // namespace
+
+size_t fwd_workspace_bytes(const FwdParams& p)
+{
+    if (p.batch == 0 || p.dim == 0 || p.seqlen == 0) return 0;
+    const Shape s = pick_shape(p);
+    if (s.nseg <= 1) return 0;
+    return (carry_floats(p, s.nseg) + (size_t)s.nseg * p.batch * p.dim) * sizeof(float);
+}
+
+hipError_t launch_fwd(FwdParams p, void* workspace, hipStream_t stream)
 {
     if (p.batch == 0 || p.dim == 0 || p.seqlen == 0) return hipSuccess;
-    const int w = pick_waves_log2(p);
-    return p.dtype == 0 ? launch_fwd_rowlane_f32(p, w, stream) : launch_fwd_rowlane_bf16(p, w, stream);
+    const Shape s = pick_shape(p);
+    auto launch = [&](const FwdParams& q) {
+        return q.dtype == 0 ? launch_fwd_rowlane_f32(q, s.waves_log2, stream)
+                            : launch_fwd_rowlane_bf16(q, s.waves_log2, stream);
+    };
+    p.nseg = s.nseg;
+    p.seg_tiles = s.seg_tiles;
+    p.summary_only = 0;
+    p.carry = nullptr;
+    p.dsum = nullptr;
+    if (s.nseg > 1) {
+        if (!workspace) return hipErrorInvalidValue;
+        p.carry = static_cast<float*>(workspace);
+        p.dsum = p.carry + carry_floats(p, s.nseg);
+        FwdParams q = p;
+        q.summary_only = 1;
+        hipError_t e = launch(q);
+        if (e != hipSuccess) return e;
+        e = launch_carry_chain(p, stream);
+        if (e != hipSuccess) return e;
+    }
+    return launch(p);
 }
 
 }  // namespace lbscan

@@ -25,7 +25,18 @@ struct FwdParams {
     void* y;              // element type = dtype, or fp32 when y_is_f32
     int y_is_f32;         // write y as fp32 whatever dtype says (first pass of the two-pass scan)
     int force_waves_log2; // >= 0: override the state-split heuristic (tests, tuning)
+    int force_nseg;       // >= 1: override the number of segments a row is cut into
+    // Long rows are cut into nseg segments of seg_tiles tiles (16 tokens each), one
+    // block per (64 rows, segment).  carry: (nseg, B*D, N) states entering each
+    // segment (read by the full pass; written by the summary pass as the states a
+    // segment reaches from zero); dsum: (nseg, B*D) sum of time steps per segment.
+    int nseg, seg_tiles;
+    int summary_only;
+    float* carry;         // nullable when nseg == 1
+    float* dsum;
 };
+
+constexpr int kTileTokens = 16;   // tokens per tile of the row-per-lane kernels
 
 // Window lengths with a compiled kernel.
 inline bool window_supported(int M) { return M == 1 || M == 2 || M == 4 || M == 8 || M == 16; }
@@ -35,7 +46,14 @@ inline bool window_supported(int M) { return M == 1 || M == 2 || M == 4 || M == 
 hipError_t launch_fwd_rowlane_f32(const FwdParams& p, int waves_log2, hipStream_t stream);
 hipError_t launch_fwd_rowlane_bf16(const FwdParams& p, int waves_log2, hipStream_t stream);
 
-// Picks the launch shape for the sizes in p and launches the forward kernel.
-hipError_t launch_fwd(const FwdParams& p, hipStream_t stream);
+// Picks the launch shape for the sizes in p and launches the forward pass
+// (several kernels when rows are cut into segments).  workspace must hold
+// fwd_workspace_bytes(p) bytes when that is non-zero.
+hipError_t launch_fwd(FwdParams p, void* workspace, hipStream_t stream);
+size_t fwd_workspace_bytes(const FwdParams& p);
+
+// Chains the per-segment summaries into the states entering each segment
+// (lbscan_carry.hip): carry[s] <- exclusive scan over s of (exp(A*dsum), carry).
+hipError_t launch_carry_chain(const FwdParams& p, hipStream_t stream);
 
 }  // namespace lbscan

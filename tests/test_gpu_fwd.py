@@ -67,6 +67,52 @@ def test_every_state_split_variant(lb, oracle, waves_log2):
         lb.lbscan_set_option("waves_log2", -1)
 
 
+@pytest.mark.parametrize("segments", [2, 3, 7])
+def test_rows_cut_into_segments(lb, oracle, segments):
+    """Long rows with few channels are cut into segments scanned in parallel
+    (summary pass, carry chain, full pass); force several cuts."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    lb.lbscan_set_option("segments", segments)
+    try:
+        for (B, D, N, L, M) in [(1, 70, 16, 333, 4), (2, 64, 8, 128, 8), (1, 130, 16, 97, 16), (1, 64, 16, 700, 1)]:
+            s = make_inputs(B, D, N, L, seed=6000 + D + L, random_A=True)
+            _run_fwd(lb, oracle, s, window=M)
+            _run_fwd(lb, oracle, s, window=M, reverse=True)
+        s = make_inputs(1, 96, 16, 256, seed=6100, dtype="bf16")
+        _run_fwd(lb, oracle, s, window=8, dtype="bf16")
+        sf = make_inputs(1, 70, 16, 333, seed=6200, random_A=True)
+        sb = make_inputs(1, 70, 16, 333, seed=6201, random_A=True)
+        _run_bidir(lb, oracle, sf, sb)
+        sf = make_inputs(1, 64, 16, 200, seed=6300, dtype="bf16")
+        sb = make_inputs(1, 64, 16, 200, seed=6301, dtype="bf16")
+        _run_bidir(lb, oracle, sf, sb, dtype="bf16")
+    finally:
+        lb.lbscan_set_option("segments", 0)
+
+
+def test_long_rows_pick_segments_by_themselves(lb, oracle):
+    from gpu_util import fwd_inputs, to_device
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(1, 64, 16, 5000, seed=6400)
+    dev = to_device(s, "fp32")
+    a = lb.make_args(**fwd_inputs(dev), window=4)
+    assert lb.lbscan_workspace_bytes(a, 0) > 0          # segmented: needs scratch
+    _run_fwd(lb, oracle, s, window=4)
+    _run_fwd(lb, oracle, s, window=16, reverse=True)
+
+
+def test_missing_workspace_is_an_error(lb):
+    import ctypes
+    import torch
+    from gpu_util import fwd_inputs, to_device
+    from paper_2506_15976_amd.inputs import make_inputs
+    dev = to_device(make_inputs(1, 64, 16, 5000, seed=6500), "fp32")
+    y = torch.empty_like(dev["x"])
+    a = lb.make_args(**fwd_inputs(dev), window=4, y=y)
+    rc = lb.load().lbscan_fwd(ctypes.byref(a), None)
+    assert rc == -3
+
+
 def test_optional_arguments_absent(lb, oracle):
     from paper_2506_15976_amd.inputs import make_inputs
     s = make_inputs(2, 96, 16, 61, seed=77, with_z=False)
