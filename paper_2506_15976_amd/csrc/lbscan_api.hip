@@ -79,6 +79,7 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     p.force_waves_log2 = tuning_waves_log2();
     p.force_nseg = tuning_nseg();
     p.nseg = 1; p.seg_tiles = 0; p.summary_only = 0; p.carry = nullptr; p.dsum = nullptr;
+    p.ckpt = nullptr; p.cum = nullptr;
     return p;
 }
 
@@ -139,13 +140,47 @@ int lbscan_bidir_fwd(const lbscan_args* fs, const lbscan_args* bs, void* hip_str
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bidir_fwd pass 2");
 }
 
-int lbscan_bwd(const lbscan_args* fwd_args, const void* dout,
+int lbscan_bwd(const lbscan_args* a, const void* dout,
                void* dx, void* ddelta, void* dz, void* dBm, void* dCm,
                float* dA, float* dDskip, float* ddelta_bias, void* hip_stream)
 {
-    (void)fwd_args; (void)dout; (void)dx; (void)ddelta; (void)dz; (void)dBm; (void)dCm;
-    (void)dA; (void)dDskip; (void)ddelta_bias; (void)hip_stream;
-    return LBSCAN_EUNSUPPORTED;
+    bool empty;
+    int rc = check_args(a, false, &empty);
+    if (rc != LBSCAN_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (!dA || !dBm || !dCm) {
+        if ((long)a->dim * a->dstate > 0 && !dA) return LBSCAN_EINVAL;
+        if ((long)a->batch * a->dstate * a->seqlen > 0 && (!dBm || !dCm)) return LBSCAN_EINVAL;
+    }
+    if ((a->Dskip && !dDskip) || (a->delta_bias && !ddelta_bias)) return LBSCAN_EINVAL;
+    if (empty) {
+        // nothing flows back: the per-channel sums are still overwritten (with zeros)
+        hipError_t e = lbscan::launch_zero(dA, (long)a->dim * a->dstate, s);
+        if (e == hipSuccess) e = lbscan::launch_zero(dDskip, a->dim, s);
+        if (e == hipSuccess) e = lbscan::launch_zero(ddelta_bias, a->dim, s);
+        return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bwd");
+    }
+    if (!dout || !dx || !ddelta || (a->z && !dz)) return LBSCAN_EINVAL;
+    const void* ptrs[] = {dout, dx, ddelta, dz, dBm, dCm, dA, dDskip, ddelta_bias};
+    for (const void* q : ptrs)
+        if (q && !aligned4(q)) return LBSCAN_EINVAL;
+    const int M = effective_window(a->window, a->seqlen);
+    if (M == 0) return LBSCAN_EUNSUPPORTED;
+    lbscan::FwdParams f = to_params(a, M);
+    const size_t need = lbscan::bwd_workspace_bytes(f);
+    if (need && (!a->workspace || a->workspace_bytes < need || !aligned4(a->workspace)))
+        return LBSCAN_EWORKSPACE;
+    lbscan::BwdParams p;
+    p.batch = f.batch; p.dim = f.dim; p.dstate = f.dstate; p.seqlen = f.seqlen;
+    p.window = M; p.dtype = f.dtype; p.softplus = f.softplus; p.reverse = f.reverse;
+    p.x = f.x; p.delta = f.delta; p.Bm = f.Bm; p.Cm = f.Cm; p.z = f.z;
+    p.A = f.A; p.Dskip = f.Dskip; p.bias = f.bias;
+    p.dout = dout; p.dx = dx; p.ddelta = ddelta; p.dz = a->z ? dz : nullptr;
+    p.dBacc = nullptr; p.dCacc = nullptr;
+    p.dA = dA; p.dDskip = a->Dskip ? dDskip : nullptr; p.dbias = a->delta_bias ? ddelta_bias : nullptr;
+    p.ckpt = nullptr;
+    hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, s);
+    return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bwd");
 }
 
 size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
@@ -158,6 +193,8 @@ size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
     switch (which) {
         case LBSCAN_WS_FWD:
             return lbscan::fwd_workspace_bytes(to_params(a, M));
+        case LBSCAN_WS_BWD:
+            return lbscan::bwd_workspace_bytes(to_params(a, M));
         case LBSCAN_WS_BIDIR:
             return (a->dtype == LBSCAN_FP32 ? 0 : bdl * sizeof(float)) +
                    lbscan::fwd_workspace_bytes(to_params(a, 1));

@@ -30,7 +30,20 @@ carry_chain_kernel(float* __restrict__ carry, const float* __restrict__ dsum,
     }
 }
 
+__global__ void __launch_bounds__(256) zero_kernel(float* __restrict__ dst, long n)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = 0.0f;
+}
+
 }  // namespace
+
+hipError_t launch_zero(float* dst, long n, hipStream_t stream)
+{
+    if (n <= 0 || !dst) return hipSuccess;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, dst, n);
+    return hipGetLastError();
+}
 
 hipError_t launch_carry_chain(const FwdParams& p, hipStream_t stream)
 {

@@ -108,4 +108,48 @@ __device__ __forceinline__ void store_quad(T* __restrict__ base, long i, long lo
     }
 }
 
+// One quad of a (rows, L) tensor.  `base` is uniform, `off` the element offset of
+// quad element 0 and `ph` its token index.  The fast form is one unconditional
+// quad load.  The checked form zeroes elements whose token index ph + e is outside
+// [0, L); it loads from a clamped (always valid) address and selects afterwards,
+// so that no load sits behind a divergent branch: a load that is conditionally
+// re-issued into the same registers would force the compiler to wait for the
+// first one and serialise the prefetch.
+template <typename T>
+__device__ __forceinline__ void quad_load_fast(const T* __restrict__ base, long off, float out[4])
+{
+    const Quad<T> q = *reinterpret_cast<const Quad<T>*>(base + off);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) out[e] = to_f32(q.v[e]);
+}
+
+template <typename T>
+__device__ __forceinline__ void quad_load_checked(const T* __restrict__ base, long off, int ph,
+                                                  int L, float out[4])
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int t = ph + e;
+        const int tc = t < 0 ? 0 : (t >= L ? L - 1 : t);
+        const float v = to_f32(base[off + (tc - ph)]);
+        out[e] = (t == tc) ? v : 0.0f;
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void quad_store(T* __restrict__ base, long off, bool fast,
+                                           int ph, int L, const float in[4])
+{
+    if (fast) {
+        Quad<T> q;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) q.v[e] = from_f32<T>(in[e]);
+        *reinterpret_cast<Quad<T>*>(base + off) = q;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (ph + e >= 0 && ph + e < L) base[off + e] = from_f32<T>(in[e]);
+    }
+}
+
 }  // namespace lbscan

@@ -83,4 +83,66 @@ hipError_t launch_fwd(FwdParams p, void* workspace, hipStream_t stream)
     return launch(p);
 }
 
+// ---- backward ----------------------------------------------------------------
+
+static size_t ckpt_floats(const FwdParams& f)
+{
+    const size_t ntiles = (f.seqlen + kTileTokens - 1) / kTileTokens;
+    return ntiles * f.batch * f.dim * (size_t)f.dstate;
+}
+
+size_t bwd_workspace_bytes(const FwdParams& f)
+{
+    if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return 0;
+    const size_t ntiles = (f.seqlen + kTileTokens - 1) / kTileTokens;
+    size_t fl = ckpt_floats(f) + ntiles * f.batch * f.dim;           // ckpt + cum
+    if (f.dtype != 0) fl += 2 * (size_t)f.batch * f.dstate * f.seqlen;   // fp32 dBm, dCm
+    return fl * sizeof(float);
+}
+
+hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
+                      hipStream_t stream)
+{
+    if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return hipSuccess;
+    if (!workspace) return hipErrorInvalidValue;
+    const size_t ntiles = (f.seqlen + kTileTokens - 1) / kTileTokens;
+    const long bnl = (long)f.batch * f.dstate * f.seqlen;
+    float* ckpt = static_cast<float*>(workspace);
+    float* cum = ckpt + ckpt_floats(f);
+    float* acc = cum + ntiles * f.batch * f.dim;
+    p.dBacc = f.dtype == 0 ? static_cast<float*>(dBm) : acc;
+    p.dCacc = f.dtype == 0 ? static_cast<float*>(dCm) : acc + bnl;
+    p.ckpt = ckpt;
+
+    hipError_t e;
+    if ((e = launch_zero(p.dBacc, bnl, stream)) != hipSuccess) return e;
+    if ((e = launch_zero(p.dCacc, bnl, stream)) != hipSuccess) return e;
+    if ((e = launch_zero(p.dA, (long)f.dim * f.dstate, stream)) != hipSuccess) return e;
+    if ((e = launch_zero(p.dDskip, f.dim, stream)) != hipSuccess) return e;
+    if ((e = launch_zero(p.dbias, f.dim, stream)) != hipSuccess) return e;
+
+    // checkpoint pass: the forward kernel in summary mode over whole rows
+    FwdParams q = f;
+    q.force_nseg = 1;
+    const Shape s = pick_shape(q);
+    q.nseg = 1;
+    q.seg_tiles = (int)ntiles;
+    q.summary_only = 1;
+    q.carry = nullptr;
+    q.dsum = nullptr;
+    q.ckpt = ckpt;
+    q.cum = cum;
+    e = q.dtype == 0 ? launch_fwd_rowlane_f32(q, s.waves_log2, stream)
+                     : launch_fwd_rowlane_bf16(q, s.waves_log2, stream);
+    if (e != hipSuccess) return e;
+
+    e = f.dtype == 0 ? launch_bwd_rowlane_f32(p, stream) : launch_bwd_rowlane_bf16(p, stream);
+    if (e != hipSuccess) return e;
+    if (f.dtype != 0) {
+        if ((e = launch_convert_bf16(p.dBacc, dBm, bnl, stream)) != hipSuccess) return e;
+        if ((e = launch_convert_bf16(p.dCacc, dCm, bnl, stream)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 }  // namespace lbscan

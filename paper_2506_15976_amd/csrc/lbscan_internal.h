@@ -34,6 +34,38 @@ struct FwdParams {
     int summary_only;
     float* carry;         // nullable when nseg == 1
     float* dsum;
+    // summary pass only: per-tile checkpoints for the backward pass (nullable):
+    // ckpt (ntiles, B*D, N) state at the start of each tile, cum (ntiles, B*D)
+    // time-step sum up to there, both counted from the start of the segment
+    float* ckpt;
+    float* cum;
+};
+
+// Arguments of one backward launch: the forward inputs plus the gradient tensors.
+struct BwdParams {
+    int batch, dim, dstate, seqlen;
+    int window;
+    int dtype;
+    int softplus;
+    int reverse;
+    const void* x;
+    const void* delta;
+    const void* Bm;
+    const void* Cm;
+    const void* z;        // nullable
+    const float* A;
+    const float* Dskip;   // nullable
+    const float* bias;    // nullable
+    const void* dout;
+    void* dx;
+    void* ddelta;
+    void* dz;             // nullable iff z is
+    float* dBacc;         // (B,N,L) fp32, zeroed: dBm accumulates here
+    float* dCacc;
+    float* dA;            // (D,N) zeroed
+    float* dDskip;        // (D) zeroed, nullable
+    float* dbias;         // (D) zeroed, nullable
+    const float* ckpt;    // (ntiles, B*D, N): f at the first step of every tile
 };
 
 constexpr int kTileTokens = 16;   // tokens per tile of the row-per-lane kernels
@@ -51,6 +83,22 @@ hipError_t launch_fwd_rowlane_bf16(const FwdParams& p, int waves_log2, hipStream
 // fwd_workspace_bytes(p) bytes when that is non-zero.
 hipError_t launch_fwd(FwdParams p, void* workspace, hipStream_t stream);
 size_t fwd_workspace_bytes(const FwdParams& p);
+
+// Backward kernels (lbscan_bwd_rowlane.inc), one translation unit per storage type.
+hipError_t launch_bwd_rowlane_f32(const BwdParams& p, hipStream_t stream);
+hipError_t launch_bwd_rowlane_bf16(const BwdParams& p, hipStream_t stream);
+hipError_t launch_convert_f32(const float* src, void* dst, long n, hipStream_t stream);
+hipError_t launch_convert_bf16(const float* src, void* dst, long n, hipStream_t stream);
+// Sets n floats to zero with a kernel (a memset node must not be recorded into
+// a captured graph).
+hipError_t launch_zero(float* dst, long n, hipStream_t stream);
+
+// Whole backward pass: zero the accumulators, checkpoint pass, backward kernel,
+// conversion of dBm / dCm when the storage type is not fp32.  dBm / dCm are the
+// caller's outputs; workspace must hold bwd_workspace_bytes(f) bytes.
+hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
+                      hipStream_t stream);
+size_t bwd_workspace_bytes(const FwdParams& f);
 
 // Chains the per-segment summaries into the states entering each segment
 // (lbscan_carry.hip): carry[s] <- exclusive scan over s of (exp(A*dsum), carry).

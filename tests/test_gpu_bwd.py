@@ -1,0 +1,106 @@
+"""GPU parity of lbscan_bwd against the fp64 CPU oracle (itself pinned by finite
+differences), every gradient, element by element, through the C ABI."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+GRADS = ("dx", "ddelta", "dz", "dBm", "dCm", "dA", "dDskip", "ddelta_bias")
+
+
+@pytest.fixture(scope="module")
+def lb():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2506_15976_amd as pkg
+    pkg.load()
+    return pkg
+
+
+def _run_bwd(lb, oracle, s, *, window, dtype="fp32", reverse=False, softplus=True):
+    import torch
+    from gpu_util import assert_close, flip_time, fwd_inputs, to_device, to_numpy
+    dev = to_device(s, dtype)
+    got = lb.lbscan_bwd(**fwd_inputs(dev), dout=dev["dout"], window=window,
+                        delta_softplus=softplus, reverse=reverse)
+    torch.cuda.synchronize()
+    src = flip_time(s) if reverse else s
+    ref = oracle.bwd(**fwd_inputs(src), dout=src["dout"], window=window, delta_softplus=softplus)
+    errs = {}
+    for k in GRADS:
+        r = ref[k]
+        if r is None:
+            assert got[k] is None
+            continue
+        if got[k] is None:
+            # no gradient is produced for an optional input that was not given
+            assert k in ("dDskip", "ddelta_bias") and s.get({"dDskip": "Dskip", "ddelta_bias": "delta_bias"}[k]) is None
+            continue
+        if reverse and r.ndim == 3:
+            r = r[..., ::-1]
+        errs[k] = assert_close(to_numpy(got[k]), r, dtype, k)
+    return errs
+
+
+@pytest.mark.parametrize("window", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("reverse", [False, True])
+def test_tiny_workload_gradients(lb, oracle, window, reverse):
+    from paper_2506_15976_amd.inputs import BASE_SEED, make_inputs
+    s = make_inputs(1, 64, 16, 256, seed=BASE_SEED, with_dout=True)
+    _run_bwd(lb, oracle, s, window=window, reverse=reverse)
+
+
+@pytest.mark.parametrize("shape", [
+    (2, 70, 16, 37), (1, 130, 16, 197), (3, 5, 16, 5), (2, 64, 16, 1), (2, 33, 16, 17),
+    (1, 64, 8, 50), (2, 20, 3, 29), (1, 7, 1, 63),
+])
+@pytest.mark.parametrize("window", [1, 4, 8])
+def test_ragged_shapes_gradients(lb, oracle, shape, window):
+    from paper_2506_15976_amd.inputs import make_inputs
+    B, D, N, L = shape
+    s = make_inputs(B, D, N, L, seed=2234 + B * 7 + D + L, random_A=True, with_dout=True)
+    _run_bwd(lb, oracle, s, window=window)
+    _run_bwd(lb, oracle, s, window=window, reverse=True)
+
+
+def test_gradients_without_optionals(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(2, 96, 16, 61, seed=177, with_z=False, with_dout=True)
+    s["Dskip"] = None
+    s["delta_bias"] = None
+    _run_bwd(lb, oracle, s, window=4)
+    s2 = make_inputs(2, 96, 16, 61, seed=178, with_dout=True)
+    s2["delta"] = np.abs(s2["delta"]) * 0.2 + 0.01
+    s2["delta_bias"] = None
+    _run_bwd(lb, oracle, s2, window=4, softplus=False)
+
+
+def test_gradients_bf16_storage(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_inputs
+    for L in (64, 197, 33):
+        s = make_inputs(2, 96, 16, L, seed=1300 + L, dtype="bf16", with_dout=True)
+        _run_bwd(lb, oracle, s, window=8, dtype="bf16")
+
+
+@pytest.mark.parametrize("name", ["vim_small", "wsi_bag"])
+def test_full_size_gradients(lb, oracle, name):
+    from paper_2506_15976_amd.inputs import WORKLOADS, make_workload
+    w = WORKLOADS[name]
+    s = make_workload(name)
+    errs = _run_bwd(lb, oracle, s, window=w["window"], dtype=w["dtype"])
+    print(name, {k: f"{v:.2e}" for k, v in errs.items()})
+
+
+def test_missing_workspace_is_an_error(lb):
+    import ctypes
+    import torch
+    from gpu_util import fwd_inputs, to_device
+    from paper_2506_15976_amd.inputs import make_inputs
+    dev = to_device(make_inputs(1, 64, 16, 64, seed=1, with_dout=True), "fp32")
+    a = lb.make_args(**fwd_inputs(dev), window=4)
+    o = {k: torch.empty_like(dev[v]) for k, v in (("dx", "x"), ("dd", "x"), ("dz", "x"), ("dB", "Bm"),
+                                                  ("dC", "Cm"), ("dA", "A"), ("dD", "Dskip"), ("db", "delta_bias"))}
+    rc = lb.load().lbscan_bwd(ctypes.byref(a), dev["dout"].data_ptr(), o["dx"].data_ptr(), o["dd"].data_ptr(),
+                              o["dz"].data_ptr(), o["dB"].data_ptr(), o["dC"].data_ptr(), o["dA"].data_ptr(),
+                              o["dD"].data_ptr(), o["db"].data_ptr(), None)
+    assert rc == -3
