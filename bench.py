@@ -39,6 +39,8 @@ def algorithmic_bytes(w, which="fwd"):
     par = w["dim"] * (w["dstate"] + 2) * 4
     if which == "fwd":
         return 4 * bdl * e + 2 * bnl * e + par
+    if which == "bwd":     # x, delta, z, dout read; dx, ddelta, dz written; Bm, Cm read; dBm, dCm written
+        return 7 * bdl * e + 4 * bnl * e + 2 * par
     if which == "bidir":   # pass 1: x, delta read, partial written; pass 2: x, delta, z, partial read, y written
         return (3 + 5) * bdl * e + 4 * bnl * e + 2 * par
     raise ValueError(which)
@@ -84,6 +86,7 @@ def main():
     ap.add_argument("--workload", default="vim_tiny")
     ap.add_argument("--shape", default="", help="B,D,N,L,M[,dtype]: time a custom shape instead of a named workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bwd", action="store_true", help="skip the backward-pass timing")
     ap.add_argument("--waves-log2", type=int, default=-1, help="force the state-split launch shape (tuning)")
     ap.add_argument("--segments", type=int, default=0, help="force the number of row segments (tuning)")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets to rotate over (0: enough for 640 MB)")
@@ -152,6 +155,30 @@ def main():
     assert rc == 0, f"lbscan_bidir_fwd failed: {rc}"
     ms_bidir = time_calls(bi_calls, max(a.steps // 2, 1), max(a.warmup // 2, 1))
 
+    # backward pass (training shapes; timed for every workload as extra information)
+    ms_bwd = None
+    if not a.no_bwd:
+        import torch
+        g_args, keep = [], []
+        for s_, ar in zip(sets, fwd_args):
+            dout = torch.randn_like(s_["x"])
+            outs = [torch.empty_like(s_["x"]) for _ in range(3)] + [torch.empty_like(s_["Bm"]) for _ in range(2)] + \
+                   [torch.empty_like(s_["A"]), torch.empty_like(s_["Dskip"]), torch.empty_like(s_["delta_bias"])]
+            keep.append((dout, outs))
+            g_args.append((ar, dout, outs))
+            if len(g_args) == 2:
+                break                    # two sets are enough to defeat the cache for these sizes
+        need = lb.lbscan_workspace_bytes(fwd_args[0], binding.WS_BWD)
+        ws_bwd = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
+
+        def bwd_call(ar, dout, outs):
+            ar.workspace, ar.workspace_bytes = ws_bwd.data_ptr(), need
+            rc_ = lib.lbscan_bwd(ctypes.byref(ar), dout.data_ptr(), *[o.data_ptr() for o in outs], stream)
+            ar.workspace, ar.workspace_bytes = ws_fwd.data_ptr(), ws_fwd.numel() * 4
+            return rc_
+        assert bwd_call(*g_args[0]) == 0, "lbscan_bwd failed"
+        ms_bwd = time_calls([(lambda g=g: bwd_call(*g)) for g in g_args], max(a.steps // 4, 1), max(a.warmup // 4, 1))
+
     tokens = w["batch"] * w["seqlen"]
     gbps = fwd_bytes / (ms_fwd * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get(a.workload)
@@ -190,6 +217,8 @@ def main():
         "speedup_vs_two_pass_bidir": ms_bidir / ms_fwd,
         "two_pass_bidir_ms": ms_bidir,
         "cache_hot_ms_per_step": ms_hot,
+        "bwd_ms": ms_bwd,
+        "bwd_algorithmic_gbps": None if ms_bwd is None else algorithmic_bytes(w, "bwd") / (ms_bwd * 1e-3) / 1e9,
     }
     print(json.dumps(line))
 
