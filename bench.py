@@ -23,11 +23,25 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+# Plain (unpacked) fp32 VALU issue: 256 CUs x 64 lanes x 2.4 GHz; packed FP32 is off by
+# build rule, so the 157.3 TFLOP/s figure (packed FMA) does not apply.  v_exp_f32 issues
+# at half rate on this chip (measured), i.e. it takes two issue slots.
+VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
+# Issue slots per state update of rowlane_fwd_kernel, from SQ_INSTS_VALU and
+# SQ_INSTS_VALU_TRANS_F32 of profiles/ (10.7 VALU instructions incl. 1.3 transcendental).
+FWD_SLOTS_PER_STATE_UPDATE = 12.0
 FWD_KEYS = ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")
 
-# HBM bytes per lbscan_fwd launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE,
-# scaled by the copy-kernel calibration); see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# L2-to-fabric bytes per lbscan_fwd call from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# (KiB per dispatch, summed over the launches of one call), each scaled by what the
+# same counter reads for a plain elementwise kernel that reads and writes 1 GiB
+# (bench.py --copy-calibration: FETCH_SIZE x2.0, WRITE_SIZE x1.0); profiles/ has the runs.
+MEASURED_TRAFFIC_BYTES = {
+    "vim_tiny": int((39360.4 * 2.0 + 31704.4) * 1024),
+    "vim_small": int((298360.4 * 2.0 + 125541.8) * 1024),
+    "hires_4096": int(((246061.6 + 106825.7 + 3498.6) * 2.0 + 56596.5 + 6528.6 + 6144.0) * 1024),
+    "wsi_bag": int(((162051.0 + 91369.3 + 3383.5) * 2.0 + 79656.1 + 6341.2 + 5968.0) * 1024),
+}
 
 
 def algorithmic_bytes(w, which="fwd"):
@@ -62,9 +76,11 @@ def upload(s, dtype):
     return out
 
 
-def time_calls(calls, steps, warmup):
-    """Run `calls[i % len]()` warmup + steps times on the current stream; return
-    average milliseconds per step from HIP events around the timed region."""
+def time_calls(calls, steps, warmup, per_launch=False):
+    """Run `calls[i % len]()` warmup + steps times on the current stream.  Returns the
+    average milliseconds per step from HIP events around the whole timed region and,
+    with per_launch, also the mean of per-launch durations from an event pair around
+    every launch (kernel time without the gaps between dependent launches)."""
     import torch
     for i in range(warmup):
         calls[i % len(calls)]()
@@ -75,7 +91,17 @@ def time_calls(calls, steps, warmup):
         calls[i % len(calls)]()
     e1.record()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / steps
+    region = e0.elapsed_time(e1) / steps
+    if not per_launch:
+        return region
+    n = min(steps, 200)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for i in range(n):
+        ev[i][0].record()
+        calls[i % len(calls)]()
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    return region, sum(a.elapsed_time(b) for a, b in ev) / n
 
 
 def main():
@@ -87,6 +113,8 @@ def main():
     ap.add_argument("--shape", default="", help="B,D,N,L,M[,dtype]: time a custom shape instead of a named workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bwd", action="store_true", help="skip the backward-pass timing")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB elementwise copy kernel, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--waves-log2", type=int, default=-1, help="force the state-split launch shape (tuning)")
     ap.add_argument("--segments", type=int, default=0, help="force the number of row segments (tuning)")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets to rotate over (0: enough for 640 MB)")
@@ -103,6 +131,13 @@ def main():
     from paper_2506_15976_amd.inputs import BASE_SEED, WORKLOADS, make_inputs, make_workload
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if a.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)     # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     lib = lb.load()
     lb.lbscan_set_option("waves_log2", a.waves_log2)
     lb.lbscan_set_option("segments", a.segments)
@@ -139,7 +174,7 @@ def main():
     rc = fwd_calls[0]()
     assert rc == 0, f"lbscan_fwd failed: {rc}"
 
-    ms_fwd = time_calls(fwd_calls, a.steps, a.warmup)
+    ms_fwd, ms_kernel = time_calls(fwd_calls, a.steps, a.warmup, per_launch=True)
     ms_hot = time_calls(fwd_calls[:1], a.steps, a.warmup)
 
     # two-pass global bi-directional scan on the same inputs (direction b = next slot)
@@ -180,6 +215,8 @@ def main():
         ms_bwd = time_calls([(lambda g=g: bwd_call(*g)) for g in g_args], max(a.steps // 4, 1), max(a.warmup // 4, 1))
 
     tokens = w["batch"] * w["seqlen"]
+    # average launch duration over the timed region (includes the ~5 us gap between
+    # dependent launches; an event pair per launch reads slightly more, a kernel trace less)
     gbps = fwd_bytes / (ms_fwd * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get(a.workload)
 
@@ -193,15 +230,18 @@ def main():
         sub = {k: (v[:nb] if isinstance(v, np.ndarray) and v.ndim == 3 else v) for k, v in host.items()}
         oracle.fwd(**{k: (v[:1] if isinstance(v, np.ndarray) and v.ndim == 3 else v) for k, v in host.items()},
                    window=w["window"])
-        best = 1e30
-        for _ in range(3):
-            t0 = time.perf_counter()
+        t0 = time.perf_counter()
+        oracle.fwd(**sub, window=w["window"])
+        once = time.perf_counter() - t0
+        reps = max(3, int(np.ceil(1.5 / max(once, 1e-4))))       # about 1.5 s of wall time on all cores
+        t0 = time.perf_counter()
+        for _ in range(reps):
             oracle.fwd(**sub, window=w["window"])
-            best = min(best, time.perf_counter() - t0)
-        cpu = {"value": nb * w["seqlen"] / best, "unit": "tokens/s", "cores": oracle.num_threads(),
+        per_call = (time.perf_counter() - t0) / reps
+        cpu = {"value": nb * w["seqlen"] / per_call, "unit": "tokens/s", "cores": oracle.num_threads(),
                "kind": "oracle",
-               "sample": f"fp64 oracle forward on {nb} of {w['batch']} batch entries of {a.workload}, best of 3, "
-                         f"{best:.3f} s"}
+               "sample": f"fp64 oracle forward on {nb} of {w['batch']} batch entries of {a.workload}, "
+                         f"mean of {reps} calls, {per_call:.4f} s per call"}
 
     line = {
         "metric": "lbscan_fwd_tokens_per_s", "value": tokens / (ms_fwd * 1e-3), "unit": "tokens/s",
@@ -212,7 +252,14 @@ def main():
                                f"M={w['window']} {w['dtype']} storage, forward", "input_sets_rotated": nsets},
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "rowlane_fwd_kernel", "algorithmic_bytes_per_launch": fwd_bytes},
+                     "kernel": "rowlane_fwd_kernel", "algorithmic_bytes_per_launch": fwd_bytes,
+                     "launch_ms": ms_fwd, "launch_ms_event_pairs": ms_kernel},
+        "alu_bound": {"unit": "state updates/s",
+                      "achieved": tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3),
+                      "peak": VALU_PEAK_LANE_OPS / FWD_SLOTS_PER_STATE_UPDATE,
+                      "frac": tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3) /
+                              (VALU_PEAK_LANE_OPS / FWD_SLOTS_PER_STATE_UPDATE),
+                      "note": "fp32 VALU issue bound of the forward kernel at its present instruction count"},
         "cpu_baseline": cpu,
         "speedup_vs_two_pass_bidir": ms_bidir / ms_fwd,
         "two_pass_bidir_ms": ms_bidir,

@@ -328,3 +328,23 @@ def test_oracle_rejects_bad_window(oracle):
 def test_empty_inputs(oracle):
     p = _rand_problem(1, 2, 3, 0, seed=2)
     assert oracle.fwd(**p, window=4, delta_softplus=True).shape == (1, 2, 0)
+
+
+def test_oracle_reproduces_its_frozen_small_case(oracle):
+    """Regression fixture written by tests/golden/make_golden.py from the oracle
+    (not a value from the paper, which prints none)."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mg = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mg)
+    gold = json.load(open(os.path.join(here, "golden", "lbscan_small_golden.json")))
+    p = mg.small_problem()
+    np.testing.assert_allclose(oracle.fwd(**p, window=gold["window"]), np.array(gold["fwd"]), rtol=1e-13)
+    np.testing.assert_allclose(oracle.bidir_fwd(dict(p), dict(p)), np.array(gold["bidir_self"]), rtol=1e-13)
+    dout = np.random.default_rng(424243).standard_normal(p["x"].shape)
+    g = oracle.bwd(**p, dout=dout, window=gold["window"])
+    for k, v in gold["bwd"].items():
+        np.testing.assert_allclose(g[k], np.array(v), rtol=1e-12, atol=1e-14)
