@@ -136,6 +136,31 @@ __device__ __forceinline__ void quad_load_checked(const T* __restrict__ base, lo
     }
 }
 
+// The same two loads, returning the raw quad (storage type) for later conversion.
+template <typename T>
+__device__ __forceinline__ Quad<T> quad_raw_fast(const T* __restrict__ base, long off)
+{
+    return *reinterpret_cast<const Quad<T>*>(base + off);
+}
+
+template <typename T> __device__ __forceinline__ T zero_elem();
+template <> __device__ __forceinline__ float zero_elem<float>() { return 0.0f; }
+template <> __device__ __forceinline__ bf16_t zero_elem<bf16_t>() { bf16_t z; z.bits = 0; return z; }
+
+template <typename T>
+__device__ __forceinline__ Quad<T> quad_raw_checked(const T* __restrict__ base, long off, int ph, int L)
+{
+    Quad<T> q;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int t = ph + e;
+        const int tc = t < 0 ? 0 : (t >= L ? L - 1 : t);
+        const T v = base[off + (tc - ph)];
+        q.v[e] = (t == tc) ? v : zero_elem<T>();
+    }
+    return q;
+}
+
 template <typename T>
 __device__ __forceinline__ void quad_store(T* __restrict__ base, long off, bool fast,
                                            int ph, int L, const float in[4])

@@ -7,33 +7,34 @@ namespace {
 struct Shape { int waves_log2, nseg, seg_tiles; };
 
 // The row-per-lane kernel runs one wave per (64 rows, state group, segment).
-// MI355X has 256 CUs x 4 SIMDs, and the scan is bound by VALU issue, which
-// needs several waves per SIMD to cover LDS and memory latency.
-//  * First split the N states of a row over more waves of the block (this
-//    repeats the per-token work of a row in every wave, so no further than
-//    needed for about 4 waves per SIMD).
-//  * If the rows alone cannot fill the chip even so, cut them into segments
-//    scanned in parallel: a summary launch, the carry chain, then the full
-//    pass started from the carried-in states.  That costs a second read of
-//    x, delta, Bm and ~60% more arithmetic, so only when rows are scarce.
+// MI355X has 256 CUs x 4 SIMDs; the kernel needs a few waves per SIMD to cover
+// LDS and memory latency.
+//  * The N states of a row are split over 4 waves of the block (4 states each):
+//    measured best at every workload shape (one wave with all 16 states needs
+//    256 registers; 8 waves repeat too much per-token work).
+//  * If the rows alone cannot fill the chip even with 8 waves per 64 rows, they
+//    are cut into segments scanned in parallel: a summary launch, the carry
+//    chain, then the full pass started from the carried-in states.  That costs a
+//    second read of x, delta, Bm and ~60% more arithmetic, so only when rows are
+//    scarce.
 Shape pick_shape(const FwdParams& p)
 {
     const long nrb = (long)((p.dim + 63) / 64) * p.batch;
     const int max_log2 = p.dstate > 8 ? 3 : (p.dstate > 4 ? 2 : (p.dstate > 2 ? 1 : 0));
-    const int ntiles = (p.seqlen + kTileTokens - 1) / kTileTokens;
+    const int ntiles = (p.seqlen + kFwdTileTokens - 1) / kFwdTileTokens;
     Shape s{0, 1, ntiles};
-    while (s.waves_log2 < max_log2 && (nrb << s.waves_log2) < 4096) ++s.waves_log2;
+    s.waves_log2 = max_log2 < 2 ? max_log2 : 2;
     long want_seg = 1;
     if ((nrb << max_log2) < 2048) {
         const int wl = max_log2 < 2 ? max_log2 : 2;
         s.waves_log2 = wl;
-        want_seg = (6144 + (nrb << wl) - 1) / (nrb << wl);
+        want_seg = (2560 + (nrb << wl) - 1) / (nrb << wl);       // about 2.5 waves per SIMD (measured best)
     }
     if (p.force_waves_log2 >= 0) s.waves_log2 = p.force_waves_log2 < max_log2 ? p.force_waves_log2 : max_log2;
     if (p.force_nseg >= 1) want_seg = p.force_nseg;
     if (want_seg > 1) {
         int st = (int)((ntiles + want_seg - 1) / want_seg);
-        if (p.force_nseg < 1 && st < 4) st = 4;               // at least 64 tokens per segment
+        if (p.force_nseg < 1 && st < 2) st = 2;               // at least 64 tokens per segment
         if (st < 1) st = 1;
         s.seg_tiles = st;
         s.nseg = (ntiles + st - 1) / st;
@@ -126,7 +127,7 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
     q.force_nseg = 1;
     const Shape s = pick_shape(q);
     q.nseg = 1;
-    q.seg_tiles = (int)ntiles;
+    q.seg_tiles = (f.seqlen + kFwdTileTokens - 1) / kFwdTileTokens;
     q.summary_only = 1;
     q.carry = nullptr;
     q.dsum = nullptr;

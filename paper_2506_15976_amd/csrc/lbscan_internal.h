@@ -68,7 +68,8 @@ struct BwdParams {
     const float* ckpt;    // (ntiles, B*D, N): f at the first step of every tile
 };
 
-constexpr int kTileTokens = 16;   // tokens per tile of the row-per-lane kernels
+constexpr int kTileTokens = 16;      // tokens per tile of the backward kernel = checkpoint spacing
+constexpr int kFwdTileTokens = 32;   // tokens per tile of the forward kernel (128 bytes of an fp32 row)
 
 // Window lengths with a compiled kernel.
 inline bool window_supported(int M) { return M == 1 || M == 2 || M == 4 || M == 8 || M == 16; }
