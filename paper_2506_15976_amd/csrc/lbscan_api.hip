@@ -79,7 +79,7 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     p.force_waves_log2 = tuning_waves_log2();
     p.force_nseg = tuning_nseg();
     p.nseg = 1; p.seg_tiles = 0; p.summary_only = 0; p.carry = nullptr; p.dsum = nullptr;
-    p.ckpt = nullptr; p.cum = nullptr;
+    p.ckpt = nullptr; p.cum = nullptr; p.dout = nullptr; p.psi = nullptr;
     return p;
 }
 
@@ -178,7 +178,7 @@ int lbscan_bwd(const lbscan_args* a, const void* dout,
     p.dout = dout; p.dx = dx; p.ddelta = ddelta; p.dz = a->z ? dz : nullptr;
     p.dBacc = nullptr; p.dCacc = nullptr;
     p.dA = dA; p.dDskip = a->Dskip ? dDskip : nullptr; p.dbias = a->delta_bias ? ddelta_bias : nullptr;
-    p.ckpt = nullptr;
+    p.ckpt = nullptr; p.nseg = 1; p.seg_tiles = 0; p.cum = nullptr; p.carry = nullptr; p.psi_in = nullptr;
     hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, s);
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bwd");
 }

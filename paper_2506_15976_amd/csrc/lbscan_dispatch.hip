@@ -26,9 +26,9 @@ Shape pick_shape(const FwdParams& p)
     s.waves_log2 = max_log2 < 2 ? max_log2 : 2;
     long want_seg = 1;
     if ((nrb << max_log2) < 2048) {
-        const int wl = max_log2 < 2 ? max_log2 : 2;
-        s.waves_log2 = wl;
-        want_seg = (2560 + (nrb << wl) - 1) / (nrb << wl);       // about 2.5 waves per SIMD (measured best)
+        // three blocks per CU are resident (LDS): aim at 3 x 256 blocks in all
+        s.waves_log2 = max_log2 < 2 ? max_log2 : 2;
+        want_seg = (768 + nrb - 1) / nrb;
     }
     if (p.force_waves_log2 >= 0) s.waves_log2 = p.force_waves_log2 < max_log2 ? p.force_waves_log2 : max_log2;
     if (p.force_nseg >= 1) want_seg = p.force_nseg;
@@ -86,19 +86,40 @@ hipError_t launch_fwd(FwdParams p, void* workspace, hipStream_t stream)
 
 // ---- backward ----------------------------------------------------------------
 
-static size_t ckpt_floats(const FwdParams& f)
+namespace {
+
+struct BwdLayout {
+    Shape shape;            // segments in forward tiles (32 tokens)
+    size_t ntiles16;        // backward tiles (16 tokens) per row
+    size_t ckpt, cum, carry, dsum, psi, acc;   // float offsets into the workspace
+    size_t total;           // floats
+};
+
+BwdLayout bwd_layout(const FwdParams& f)
 {
-    const size_t ntiles = (f.seqlen + kTileTokens - 1) / kTileTokens;
-    return ntiles * f.batch * f.dim * (size_t)f.dstate;
+    BwdLayout l;
+    l.shape = pick_shape(f);
+    const size_t rows = (size_t)f.batch * f.dim, N = f.dstate;
+    l.ntiles16 = (f.seqlen + kTileTokens - 1) / kTileTokens;
+    size_t o = 0;
+    l.ckpt = o; o += l.ntiles16 * rows * N;
+    l.cum = o;  o += l.ntiles16 * rows;
+    const size_t ns = l.shape.nseg > 1 ? l.shape.nseg : 0;
+    l.carry = o; o += ns * rows * N;
+    l.dsum = o;  o += ns * rows;
+    l.psi = o;   o += ns * rows * N;
+    l.acc = o;
+    if (f.dtype != 0) o += 2 * (size_t)f.batch * N * f.seqlen;     // fp32 dBm, dCm
+    l.total = o;
+    return l;
 }
+
+}  // namespace
 
 size_t bwd_workspace_bytes(const FwdParams& f)
 {
     if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return 0;
-    const size_t ntiles = (f.seqlen + kTileTokens - 1) / kTileTokens;
-    size_t fl = ckpt_floats(f) + ntiles * f.batch * f.dim;           // ckpt + cum
-    if (f.dtype != 0) fl += 2 * (size_t)f.batch * f.dstate * f.seqlen;   // fp32 dBm, dCm
-    return fl * sizeof(float);
+    return bwd_layout(f).total * sizeof(float);
 }
 
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
@@ -106,14 +127,18 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
 {
     if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return hipSuccess;
     if (!workspace) return hipErrorInvalidValue;
-    const size_t ntiles = (f.seqlen + kTileTokens - 1) / kTileTokens;
+    const BwdLayout l = bwd_layout(f);
+    const Shape& s = l.shape;
+    float* ws = static_cast<float*>(workspace);
     const long bnl = (long)f.batch * f.dstate * f.seqlen;
-    float* ckpt = static_cast<float*>(workspace);
-    float* cum = ckpt + ckpt_floats(f);
-    float* acc = cum + ntiles * f.batch * f.dim;
-    p.dBacc = f.dtype == 0 ? static_cast<float*>(dBm) : acc;
-    p.dCacc = f.dtype == 0 ? static_cast<float*>(dCm) : acc + bnl;
-    p.ckpt = ckpt;
+    p.dBacc = f.dtype == 0 ? static_cast<float*>(dBm) : ws + l.acc;
+    p.dCacc = f.dtype == 0 ? static_cast<float*>(dCm) : ws + l.acc + bnl;
+    p.ckpt = ws + l.ckpt;
+    p.cum = ws + l.cum;
+    p.nseg = s.nseg;
+    p.seg_tiles = s.seg_tiles * (kFwdTileTokens / kTileTokens);
+    p.carry = s.nseg > 1 ? ws + l.carry : nullptr;
+    p.psi_in = s.nseg > 1 ? ws + l.psi : nullptr;
 
     hipError_t e;
     if ((e = launch_zero(p.dBacc, bnl, stream)) != hipSuccess) return e;
@@ -122,20 +147,26 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
     if ((e = launch_zero(p.dDskip, f.dim, stream)) != hipSuccess) return e;
     if ((e = launch_zero(p.dbias, f.dim, stream)) != hipSuccess) return e;
 
-    // checkpoint pass: the forward kernel in summary mode over whole rows
+    // summary pass (the forward kernel in summary mode): checkpoints of f for every
+    // 16-token tile and, when the rows are cut, the per-segment summaries of the
+    // forward and of the right-to-left recurrence
     FwdParams q = f;
-    q.force_nseg = 1;
-    const Shape s = pick_shape(q);
-    q.nseg = 1;
-    q.seg_tiles = (f.seqlen + kFwdTileTokens - 1) / kFwdTileTokens;
+    q.nseg = s.nseg;
+    q.seg_tiles = s.seg_tiles;
     q.summary_only = 1;
-    q.carry = nullptr;
-    q.dsum = nullptr;
-    q.ckpt = ckpt;
-    q.cum = cum;
+    q.ckpt = ws + l.ckpt;
+    q.cum = ws + l.cum;
+    q.carry = s.nseg > 1 ? ws + l.carry : nullptr;
+    q.dsum = s.nseg > 1 ? ws + l.dsum : nullptr;
+    q.psi = s.nseg > 1 ? ws + l.psi : nullptr;
+    q.dout = p.dout;
     e = q.dtype == 0 ? launch_fwd_rowlane_f32(q, s.waves_log2, stream)
                      : launch_fwd_rowlane_bf16(q, s.waves_log2, stream);
     if (e != hipSuccess) return e;
+    if (s.nseg > 1) {
+        if ((e = launch_carry_chain(q, stream)) != hipSuccess) return e;
+        if ((e = launch_carry_chain_reverse(q, q.psi, stream)) != hipSuccess) return e;
+    }
 
     e = f.dtype == 0 ? launch_bwd_rowlane_f32(p, stream) : launch_bwd_rowlane_bf16(p, stream);
     if (e != hipSuccess) return e;

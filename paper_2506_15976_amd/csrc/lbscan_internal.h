@@ -39,6 +39,10 @@ struct FwdParams {
     // time-step sum up to there, both counted from the start of the segment
     float* ckpt;
     float* cum;
+    // summary pass for a segmented backward pass (nullable): dout (B,D,L) in, and
+    // psi (nseg, B*D, N) out: the segment's summary of the right-to-left recurrence
+    const void* dout;
+    float* psi;
 };
 
 // Arguments of one backward launch: the forward inputs plus the gradient tensors.
@@ -65,7 +69,13 @@ struct BwdParams {
     float* dA;            // (D,N) zeroed
     float* dDskip;        // (D) zeroed, nullable
     float* dbias;         // (D) zeroed, nullable
-    const float* ckpt;    // (ntiles, B*D, N): f at the first step of every tile
+    const float* ckpt;    // (ntiles, B*D, N): f at the first step of every tile, counted
+                          // from the start of the tile's segment
+    // rows cut into nseg segments of seg_tiles backward tiles (16 tokens each):
+    int nseg, seg_tiles;
+    const float* cum;     // (ntiles, B*D): time-step sum from the segment start to the tile
+    const float* carry;   // (nseg, B*D, N): forward state entering each segment (null: zeros)
+    const float* psi_in;  // (nseg, B*D, N): psi entering each segment from the right
 };
 
 constexpr int kTileTokens = 16;      // tokens per tile of the backward kernel = checkpoint spacing
@@ -104,5 +114,7 @@ size_t bwd_workspace_bytes(const FwdParams& f);
 // Chains the per-segment summaries into the states entering each segment
 // (lbscan_carry.hip): carry[s] <- exclusive scan over s of (exp(A*dsum), carry).
 hipError_t launch_carry_chain(const FwdParams& p, hipStream_t stream);
+// The same chain over `buf` (nseg, B*D, N) walking the segments right to left.
+hipError_t launch_carry_chain_reverse(const FwdParams& p, float* buf, hipStream_t stream);
 
 }  // namespace lbscan

@@ -82,6 +82,32 @@ def test_gradients_bf16_storage(lb, oracle):
         _run_bwd(lb, oracle, s, window=8, dtype="bf16")
 
 
+@pytest.mark.parametrize("segments", [2, 3, 5])
+def test_gradients_with_rows_cut_into_segments(lb, oracle, segments):
+    """Long rows are cut into segments in the backward pass too: forward carry
+    chain for f, reverse chain for psi; force several cuts."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    lb.lbscan_set_option("segments", segments)
+    try:
+        for (B, D, N, L, M) in [(1, 70, 16, 333, 4), (2, 64, 8, 160, 8), (1, 130, 16, 97, 16), (1, 64, 16, 700, 1)]:
+            s = make_inputs(B, D, N, L, seed=7000 + D + L, random_A=True, with_dout=True)
+            _run_bwd(lb, oracle, s, window=M)
+            _run_bwd(lb, oracle, s, window=M, reverse=True)
+        s = make_inputs(1, 96, 16, 256, seed=7100, dtype="bf16", with_dout=True)
+        _run_bwd(lb, oracle, s, window=8, dtype="bf16")
+        s = make_inputs(1, 64, 16, 300, seed=7200, with_z=False, with_dout=True)
+        _run_bwd(lb, oracle, s, window=4)
+    finally:
+        lb.lbscan_set_option("segments", 0)
+
+
+def test_long_rows_gradients_pick_segments_by_themselves(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(1, 64, 16, 5000, seed=7300, with_dout=True)
+    _run_bwd(lb, oracle, s, window=4)
+    _run_bwd(lb, oracle, s, window=16, reverse=True)
+
+
 @pytest.mark.parametrize("name", ["vim_small", "wsi_bag"])
 def test_full_size_gradients(lb, oracle, name):
     from paper_2506_15976_amd.inputs import WORKLOADS, make_workload
