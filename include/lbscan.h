@@ -75,11 +75,19 @@ typedef struct lbscan_args {
     void        *y;           /* (B,D,L) out */
     void        *workspace;   /* device scratch of lbscan_workspace_bytes() bytes, or NULL if 0 */
     size_t       workspace_bytes;
+    void        *saved_state; /* optional device buffer of lbscan_workspace_bytes(args,
+                                 LBSCAN_WS_SAVED) bytes shared by a forward call and the
+                                 backward call that follows it.  lbscan_fwd fills it with
+                                 checkpoints of the forward states (when the size is not 0
+                                 for these shapes); lbscan_bwd given the same buffer starts
+                                 from them instead of recomputing them.  NULL: not used. */
+    size_t       saved_state_bytes;
 } lbscan_args;
 
 #define LBSCAN_WS_FWD   0
 #define LBSCAN_WS_BWD   1
 #define LBSCAN_WS_BIDIR 2
+#define LBSCAN_WS_SAVED 3   /* size of lbscan_args.saved_state (0: these shapes do not use it) */
 
 /* Forward pass of the locally bi-directional scan (Sec. 3.2, Eq. 7-8, on top of
  * the global forward scan of Eq. 1-3; gate and skip of Algorithm 1 fused in). */
@@ -88,7 +96,8 @@ int lbscan_fwd(const lbscan_args *args, void *hip_stream);
 /* Gradients of lbscan_fwd with respect to every input (the paper reports only
  * training throughput, Appendix B; the formulas are the reverse-mode derivative
  * of the forward definition above).  fwd_args names the forward inputs
- * (fwd_args->y is not read).  dout is the upstream gradient of out.  dz may be
+ * (fwd_args->y is not read; fwd_args->saved_state, if given, must have been filled
+ * by lbscan_fwd on the same inputs).  dout is the upstream gradient of out.  dz may be
  * NULL iff fwd_args->z is NULL.  dDskip / ddelta_bias may be NULL iff the
  * corresponding input is NULL.  All outputs are overwritten (not accumulated). */
 int lbscan_bwd(const lbscan_args *fwd_args, const void *dout,

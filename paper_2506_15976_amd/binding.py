@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblbscan.so")
 
 LBSCAN_FP32, LBSCAN_BF16 = 0, 1
-WS_FWD, WS_BWD, WS_BIDIR = 0, 1, 2
+WS_FWD, WS_BWD, WS_BIDIR, WS_SAVED = 0, 1, 2, 3
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = (
@@ -34,6 +34,7 @@ class LbscanArgs(ctypes.Structure):
         ("Cm", ctypes.c_void_p), ("z", ctypes.c_void_p), ("A", ctypes.c_void_p),
         ("Dskip", ctypes.c_void_p), ("delta_bias", ctypes.c_void_p), ("y", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("saved_state", ctypes.c_void_p), ("saved_state_bytes", ctypes.c_size_t),
     ]
 
 
@@ -109,7 +110,7 @@ def _stream(stream):
 
 
 def make_args(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, window,
-              delta_softplus=True, reverse=False, y=None, workspace=None):
+              delta_softplus=True, reverse=False, y=None, workspace=None, saved_state=None):
     """Fill a struct lbscan_args from device tensors.  Shapes: x, delta, z, y
     (B,D,L); Bm, Cm (B,N,L); A (D,N) fp32; Dskip, delta_bias (D) fp32."""
     import torch
@@ -128,13 +129,16 @@ def make_args(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, windo
         if tuple(t.shape) != shape or t.dtype != torch.float32:
             raise LbscanError(EINVAL, f"{name}: expected {shape} float32")
     for name, t in (("x", x), ("delta", delta), ("A", A), ("Bm", Bm), ("Cm", Cm), ("Dskip", Dskip),
-                    ("z", z), ("delta_bias", delta_bias), ("y", y), ("workspace", workspace)):
+                    ("z", z), ("delta_bias", delta_bias), ("y", y), ("workspace", workspace),
+                    ("saved_state", saved_state)):
         if t is not None and (not t.is_cuda or not t.is_contiguous()):
             raise LbscanError(EINVAL, f"{name} must be a contiguous device tensor")
     a = LbscanArgs(Bsz, D, N, L, int(window), code, int(bool(delta_softplus)), int(bool(reverse)),
                    _ptr(x), _ptr(delta), _ptr(Bm), _ptr(Cm), _ptr(z), _ptr(A), _ptr(Dskip),
                    _ptr(delta_bias), _ptr(y), _ptr(workspace),
-                   0 if workspace is None else workspace.numel() * workspace.element_size())
+                   0 if workspace is None else workspace.numel() * workspace.element_size(),
+                   _ptr(saved_state),
+                   0 if saved_state is None else saved_state.numel() * saved_state.element_size())
     return a
 
 
@@ -165,13 +169,22 @@ def _workspace_for(args, which, like):
     return ws
 
 
+def lbscan_saved_state(x, A, *, window):
+    """Buffer for lbscan_fwd(saved_state=...) / lbscan_bwd(saved_state=...), or None
+    when these shapes do not use one."""
+    import torch
+    a = LbscanArgs(x.shape[0], x.shape[1], A.shape[1], x.shape[2], int(window), _dtype_code(x))
+    need = lbscan_workspace_bytes(a, WS_SAVED)
+    return torch.empty((need + 3) // 4, dtype=torch.float32, device=x.device) if need else None
+
+
 def lbscan_fwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, window,
-               delta_softplus=True, reverse=False, out=None, stream=None):
+               delta_softplus=True, reverse=False, out=None, stream=None, saved_state=None):
     """out = locally bi-directional scan of the inputs (see include/lbscan.h)."""
     import torch
     y = torch.empty_like(x) if out is None else out
     a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
-                  delta_softplus=delta_softplus, reverse=reverse, y=y)
+                  delta_softplus=delta_softplus, reverse=reverse, y=y, saved_state=saved_state)
     ws = _workspace_for(a, WS_FWD, x)
     _check(load().lbscan_fwd(ctypes.byref(a), _stream(stream)), "lbscan_fwd")
     del ws
@@ -198,12 +211,12 @@ def lbscan_bidir_fwd(set_f: dict, set_b: dict, *, out=None, stream=None):
 
 
 def lbscan_bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout, window,
-               delta_softplus=True, reverse=False, stream=None):
+               delta_softplus=True, reverse=False, stream=None, saved_state=None):
     """Gradients of lbscan_fwd.  Returns a dict: dx, ddelta, dz, dBm, dCm, dA,
     dDskip, ddelta_bias (None where the input is absent)."""
     import torch
     a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
-                  delta_softplus=delta_softplus, reverse=reverse)
+                  delta_softplus=delta_softplus, reverse=reverse, saved_state=saved_state)
     if tuple(dout.shape) != tuple(x.shape) or dout.dtype != x.dtype or not dout.is_contiguous():
         raise LbscanError(EINVAL, "dout must match x")
     g = dict(

@@ -98,7 +98,13 @@ int lbscan_fwd(const lbscan_args* args, void* hip_stream)
     const size_t need = lbscan::fwd_workspace_bytes(p);
     if (need && (!args->workspace || args->workspace_bytes < need || !aligned4(args->workspace)))
         return LBSCAN_EWORKSPACE;
-    hipError_t e = lbscan::launch_fwd(p, args->workspace, static_cast<hipStream_t>(hip_stream));
+    float* saved = nullptr;
+    if (args->saved_state) {
+        const size_t sneed = lbscan::saved_state_bytes(p);
+        if (sneed && (args->saved_state_bytes < sneed || !aligned4(args->saved_state))) return LBSCAN_EWORKSPACE;
+        if (sneed) saved = static_cast<float*>(args->saved_state);
+    }
+    hipError_t e = lbscan::launch_fwd(p, args->workspace, saved, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_fwd");
 }
 
@@ -133,10 +139,10 @@ int lbscan_bidir_fwd(const lbscan_args* fs, const lbscan_args* bs, void* hip_str
         scratch += bdl * sizeof(float);
     }
     p1.reverse = 0; p1.z = nullptr; p1.y = partial; p1.y_is_f32 = 1;
-    hipError_t e = lbscan::launch_fwd(p1, scratch, s);
+    hipError_t e = lbscan::launch_fwd(p1, scratch, nullptr, s);
     if (e != hipSuccess) return hip_fail(e, "lbscan_bidir_fwd pass 1");
     p2.reverse = 1; p2.z = fs->z; p2.yprev = partial; p2.y = fs->y; p2.y_is_f32 = 0;
-    e = lbscan::launch_fwd(p2, scratch, s);
+    e = lbscan::launch_fwd(p2, scratch, nullptr, s);
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bidir_fwd pass 2");
 }
 
@@ -179,7 +185,13 @@ int lbscan_bwd(const lbscan_args* a, const void* dout,
     p.dBacc = nullptr; p.dCacc = nullptr;
     p.dA = dA; p.dDskip = a->Dskip ? dDskip : nullptr; p.dbias = a->delta_bias ? ddelta_bias : nullptr;
     p.ckpt = nullptr; p.nseg = 1; p.seg_tiles = 0; p.cum = nullptr; p.carry = nullptr; p.psi_in = nullptr;
-    hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, s);
+    const float* saved = nullptr;
+    if (a->saved_state) {
+        const size_t sneed = lbscan::saved_state_bytes(f);
+        if (sneed && (a->saved_state_bytes < sneed || !aligned4(a->saved_state))) return LBSCAN_EWORKSPACE;
+        if (sneed) saved = static_cast<const float*>(a->saved_state);
+    }
+    hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, saved, s);
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bwd");
 }
 
@@ -195,6 +207,8 @@ size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
             return lbscan::fwd_workspace_bytes(to_params(a, M));
         case LBSCAN_WS_BWD:
             return lbscan::bwd_workspace_bytes(to_params(a, M));
+        case LBSCAN_WS_SAVED:
+            return lbscan::saved_state_bytes(to_params(a, M));
         case LBSCAN_WS_BIDIR:
             return (a->dtype == LBSCAN_FP32 ? 0 : bdl * sizeof(float)) +
                    lbscan::fwd_workspace_bytes(to_params(a, 1));

@@ -57,10 +57,20 @@ size_t fwd_workspace_bytes(const FwdParams& p)
     return (carry_floats(p, s.nseg) + (size_t)s.nseg * p.batch * p.dim) * sizeof(float);
 }
 
-hipError_t launch_fwd(FwdParams p, void* workspace, hipStream_t stream)
+size_t saved_state_bytes(const FwdParams& p)
+{
+    if (p.batch == 0 || p.dim == 0 || p.seqlen == 0) return 0;
+    if (pick_shape(p).nseg > 1) return 0;
+    const size_t ntiles16 = (p.seqlen + kTileTokens - 1) / kTileTokens;
+    return ntiles16 * p.batch * p.dim * (size_t)p.dstate * sizeof(float);
+}
+
+hipError_t launch_fwd(FwdParams p, void* workspace, float* saved, hipStream_t stream)
 {
     if (p.batch == 0 || p.dim == 0 || p.seqlen == 0) return hipSuccess;
     const Shape s = pick_shape(p);
+    p.ckpt = (saved && s.nseg == 1) ? saved : nullptr;
+    p.cum = nullptr;
     auto launch = [&](const FwdParams& q) {
         return q.dtype == 0 ? launch_fwd_rowlane_f32(q, s.waves_log2, stream)
                             : launch_fwd_rowlane_bf16(q, s.waves_log2, stream);
@@ -123,7 +133,7 @@ size_t bwd_workspace_bytes(const FwdParams& f)
 }
 
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
-                      hipStream_t stream)
+                      const float* saved, hipStream_t stream)
 {
     if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return hipSuccess;
     if (!workspace) return hipErrorInvalidValue;
@@ -146,6 +156,19 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
     if ((e = launch_zero(p.dA, (long)f.dim * f.dstate, stream)) != hipSuccess) return e;
     if ((e = launch_zero(p.dDskip, f.dim, stream)) != hipSuccess) return e;
     if ((e = launch_zero(p.dbias, f.dim, stream)) != hipSuccess) return e;
+
+    if (saved && s.nseg == 1) {
+        // the forward call left the checkpoints: no summary pass
+        p.ckpt = saved;
+        p.cum = nullptr;
+        e = f.dtype == 0 ? launch_bwd_rowlane_f32(p, stream) : launch_bwd_rowlane_bf16(p, stream);
+        if (e != hipSuccess) return e;
+        if (f.dtype != 0) {
+            if ((e = launch_convert_bf16(p.dBacc, dBm, bnl, stream)) != hipSuccess) return e;
+            if ((e = launch_convert_bf16(p.dCacc, dCm, bnl, stream)) != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
 
     // summary pass (the forward kernel in summary mode): checkpoints of f for every
     // 16-token tile and, when the rows are cut, the per-segment summaries of the

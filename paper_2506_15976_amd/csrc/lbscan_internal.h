@@ -92,8 +92,13 @@ hipError_t launch_fwd_rowlane_bf16(const FwdParams& p, int waves_log2, hipStream
 // Picks the launch shape for the sizes in p and launches the forward pass
 // (several kernels when rows are cut into segments).  workspace must hold
 // fwd_workspace_bytes(p) bytes when that is non-zero.
-hipError_t launch_fwd(FwdParams p, void* workspace, hipStream_t stream);
+// saved (nullable): buffer of saved_state_bytes(p) bytes to fill with checkpoints for
+// a backward call (ignored when that size is 0).
+hipError_t launch_fwd(FwdParams p, void* workspace, float* saved, hipStream_t stream);
 size_t fwd_workspace_bytes(const FwdParams& p);
+// Bytes of the saved-state buffer, 0 when rows are cut into segments (the backward
+// pass then needs its own summary pass anyway).
+size_t saved_state_bytes(const FwdParams& p);
 
 // Backward kernels (lbscan_bwd_rowlane.inc), one translation unit per storage type.
 hipError_t launch_bwd_rowlane_f32(const BwdParams& p, hipStream_t stream);
@@ -107,8 +112,9 @@ hipError_t launch_zero(float* dst, long n, hipStream_t stream);
 // Whole backward pass: zero the accumulators, checkpoint pass, backward kernel,
 // conversion of dBm / dCm when the storage type is not fp32.  dBm / dCm are the
 // caller's outputs; workspace must hold bwd_workspace_bytes(f) bytes.
+// saved (nullable): checkpoints left by launch_fwd on the same inputs.
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
-                      hipStream_t stream);
+                      const float* saved, hipStream_t stream);
 size_t bwd_workspace_bytes(const FwdParams& f);
 
 // Chains the per-segment summaries into the states entering each segment

@@ -117,6 +117,37 @@ def test_full_size_gradients(lb, oracle, name):
     print(name, {k: f"{v:.2e}" for k, v in errs.items()})
 
 
+def test_saved_state_from_forward_gives_the_same_gradients(lb, oracle):
+    """lbscan_fwd can leave checkpoints that lbscan_bwd starts from instead of
+    recomputing them; both ways must agree with the oracle."""
+    import torch
+    from gpu_util import assert_close, flip_time, fwd_inputs, to_device, to_numpy
+    from paper_2506_15976_amd.inputs import make_inputs
+    lb.lbscan_set_option("segments", 1)      # small shapes would otherwise be cut into segments
+    try:
+        for (B, D, N, L, M, rev) in [(2, 130, 16, 197, 4, False), (3, 64, 16, 50, 8, True), (2, 70, 8, 33, 1, False)]:
+            s = make_inputs(B, D, N, L, seed=8000 + L, random_A=True, with_dout=True)
+            dev = to_device(s, "fp32")
+            saved = lb.lbscan_saved_state(dev["x"], dev["A"], window=M)
+            assert saved is not None
+            saved.fill_(float("nan"))
+            out = lb.lbscan_fwd(**fwd_inputs(dev), window=M, reverse=rev, saved_state=saved)
+            got = lb.lbscan_bwd(**fwd_inputs(dev), dout=dev["dout"], window=M, reverse=rev, saved_state=saved)
+            torch.cuda.synchronize()
+            src = flip_time(s) if rev else s
+            ref_out = oracle.fwd(**fwd_inputs(src), window=M)
+            ref = oracle.bwd(**fwd_inputs(src), dout=src["dout"], window=M)
+            assert_close(to_numpy(out), ref_out[..., ::-1] if rev else ref_out, "fp32", "out")
+            for k in GRADS:
+                r = ref[k][..., ::-1] if (rev and ref[k].ndim == 3) else ref[k]
+                assert_close(to_numpy(got[k]), r, "fp32", k)
+    finally:
+        lb.lbscan_set_option("segments", 0)
+    # long rows are cut into segments: no saved state for them
+    big = to_device(make_inputs(1, 64, 16, 5000, seed=8100), "fp32")
+    assert lb.lbscan_saved_state(big["x"], big["A"], window=4) is None
+
+
 def test_missing_workspace_is_an_error(lb):
     import ctypes
     import torch
