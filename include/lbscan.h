@@ -129,7 +129,7 @@ int lbscan_default_window(int32_t seqlen);
  *                 or 8 (clamped to what the state size allows).
  *   "segments":   0 (default) lets the library choose into how many segments a
  *                 row is cut for parallel scanning (long rows, few channels);
- *                 k >= 1 asks for k (rounded to whole 16-token tiles).  It
+ *                 k >= 1 asks for k (rounded so that segments are whole 32-token tiles).  It
  *                 changes lbscan_workspace_bytes: query after setting it.
  * Returns LBSCAN_EINVAL for an unknown name or a value out of range. */
 int lbscan_set_option(const char *name, int value);

@@ -5,10 +5,14 @@
 // segment reaches from a zero state, and the sum S_s of its time steps.  The
 // recurrence of Eq. 1 (Sec. 3.1) is linear, so the state entering segment s+1
 // is  c_{s+1} = exp(A S_s) c_s + e_s  with c_0 = 0: the product of the
-// segment's abar factors is exp(A * sum of dt).  One lane per (row, n) walks
-// the segments in order and overwrites e_s by c_s in place.  The backward pass's
-// right-to-left recurrence psi_t = abar_t (e_t + psi_{t+1}) chains the same way
-// with the segments walked from the last to the first.
+// segment's abar factors is exp(A * sum of dt).  A step of that chain is the
+// affine map c -> P c + e, and affine maps compose associatively, so a group of
+// G lanes (G a power of two, at most a wave) takes G consecutive segments of one
+// (row, n) pair, forms the running composition with a shuffle scan, and each
+// lane overwrites its e_s by the state c_s entering its segment.  Chains longer
+// than G are walked in chunks of G with the carried state passed along.  The
+// backward pass's right-to-left recurrence psi_t = abar_t (e_t + psi_{t+1})
+// chains the same way with the segments walked from the last to the first.
 #include "lbscan_device.h"
 #include "lbscan_internal.h"
 
@@ -17,19 +21,36 @@ namespace {
 
 __global__ void __launch_bounds__(256)
 carry_chain_kernel(float* __restrict__ carry, const float* __restrict__ dsum,
-                   const float* __restrict__ A, int rows, int D, int N, int nseg, int reverse)
+                   const float* __restrict__ A, int rows, int D, int N, int nseg, int reverse,
+                   int G)
 {
-    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;   // (row, n)
-    if (i >= (long)rows * N) return;
+    const long npairs = (long)rows * N;
+    const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int g = (int)(t % G);                       // segment within the chunk
+    const long pair = t / G;                          // (row, n)
+    const bool valid = pair < npairs;
+    const long i = valid ? pair : npairs - 1;         // clamped: every lane shuffles
     const int row = (int)(i / N), n = (int)(i % N);
     const float a2 = A[(long)(row % D) * N + n] * kLog2e;
-    float c = 0.0f;
-    for (int ss = 0; ss < nseg; ++ss) {
-        const int s = reverse ? nseg - 1 - ss : ss;
-        const long k = (long)s * rows * N + i;
-        const float e = carry[k];
-        carry[k] = c;
-        c = fmaf(fast_exp2(a2 * dsum[(long)s * rows + row]), c, e);
+    float cin = 0.0f;                                 // state entering the chunk
+    for (int base = 0; base < nseg; base += G) {
+        const int ss = base + g;
+        const bool on = ss < nseg;
+        const int s = reverse ? nseg - 1 - (on ? ss : 0) : (on ? ss : 0);
+        const long k = (long)s * npairs + i;
+        // lanes past the end of the chain hold the identity map
+        float e = on ? carry[k] : 0.0f;
+        float P = on ? fast_exp2(a2 * dsum[(long)s * rows + row]) : 1.0f;
+        // inclusive scan: lane g ends with the composition of segments base..base+g
+        for (int d = 1; d < G; d <<= 1) {
+            const float Pp = __shfl_up(P, d, G), ep = __shfl_up(e, d, G);
+            if (g >= d) { e = fmaf(P, ep, e); P *= Pp; }
+        }
+        const float Pm = __shfl_up(P, 1, G), em = __shfl_up(e, 1, G);
+        const float c = g == 0 ? cin : fmaf(Pm, cin, em);
+        if (on && valid) carry[k] = c;
+        const float Pl = __shfl(P, G - 1, G), el = __shfl(e, G - 1, G);
+        cin = fmaf(Pl, cin, el);
     }
 }
 
@@ -37,6 +58,15 @@ __global__ void __launch_bounds__(256) zero_kernel(float* __restrict__ dst, long
 {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = 0.0f;
+}
+
+// lanes per (row, n) pair: the smallest power of two that covers the chain, one
+// wave at most
+int chain_group(int nseg)
+{
+    int G = 1;
+    while (G < nseg && G < 64) G <<= 1;
+    return G;
 }
 
 }  // namespace
@@ -53,9 +83,10 @@ hipError_t launch_carry_chain(const FwdParams& p, hipStream_t stream)
     const int rows = p.batch * p.dim;
     const long n = (long)rows * p.dstate;
     if (n == 0) return hipSuccess;
-    const unsigned blocks = (unsigned)((n + 255) / 256);
+    const int G = chain_group(p.nseg);
+    const unsigned blocks = (unsigned)((n * G + 255) / 256);
     hipLaunchKernelGGL(carry_chain_kernel, dim3(blocks), dim3(256), 0, stream,
-                       p.carry, p.dsum, p.A, rows, p.dim, p.dstate, p.nseg, 0);
+                       p.carry, p.dsum, p.A, rows, p.dim, p.dstate, p.nseg, 0, G);
     return hipGetLastError();
 }
 
@@ -64,9 +95,10 @@ hipError_t launch_carry_chain_reverse(const FwdParams& p, float* buf, hipStream_
     const int rows = p.batch * p.dim;
     const long n = (long)rows * p.dstate;
     if (n == 0) return hipSuccess;
-    const unsigned blocks = (unsigned)((n + 255) / 256);
+    const int G = chain_group(p.nseg);
+    const unsigned blocks = (unsigned)((n * G + 255) / 256);
     hipLaunchKernelGGL(carry_chain_kernel, dim3(blocks), dim3(256), 0, stream,
-                       buf, p.dsum, p.A, rows, p.dim, p.dstate, p.nseg, 1);
+                       buf, p.dsum, p.A, rows, p.dim, p.dstate, p.nseg, 1, G);
     return hipGetLastError();
 }
 

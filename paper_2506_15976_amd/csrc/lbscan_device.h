@@ -70,44 +70,6 @@ template <typename T> struct Quad;
 template <> struct __attribute__((packed, aligned(4))) Quad<float> { float v[4]; };
 template <> struct __attribute__((packed, aligned(4))) Quad<bf16_t> { bf16_t v[4]; };
 
-// Loads elements [i, i+4) of a row-major tensor into fp32, zero where the
-// element index e (0..3) fails lo <= i+e < hi.  `vec_ok` says the tensor base
-// and i are such that the quad is 4-byte aligned.
-template <typename T>
-__device__ __forceinline__ void load_quad(const T* __restrict__ base, long i, long lo, long hi,
-                                          bool vec_ok, float out[4])
-{
-    if (vec_ok && i >= lo && i + 4 <= hi) {
-        Quad<T> q = *reinterpret_cast<const Quad<T>*>(base + i);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) out[e] = to_f32(q.v[e]);
-    } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            long k = i + e;
-            out[e] = (k >= lo && k < hi) ? to_f32(base[k]) : 0.0f;
-        }
-    }
-}
-
-template <typename T>
-__device__ __forceinline__ void store_quad(T* __restrict__ base, long i, long lo, long hi,
-                                           bool vec_ok, const float in[4])
-{
-    if (vec_ok && i >= lo && i + 4 <= hi) {
-        Quad<T> q;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) q.v[e] = from_f32<T>(in[e]);
-        *reinterpret_cast<Quad<T>*>(base + i) = q;
-    } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            long k = i + e;
-            if (k >= lo && k < hi) base[k] = from_f32<T>(in[e]);
-        }
-    }
-}
-
 // One quad of a (rows, L) tensor.  `base` is uniform, `off` the element offset of
 // quad element 0 and `ph` its token index.  The fast form is one unconditional
 // quad load.  The checked form zeroes elements whose token index ph + e is outside

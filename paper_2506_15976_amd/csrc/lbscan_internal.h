@@ -26,7 +26,7 @@ struct FwdParams {
     int y_is_f32;         // write y as fp32 whatever dtype says (first pass of the two-pass scan)
     int force_waves_log2; // >= 0: override the state-split heuristic (tests, tuning)
     int force_nseg;       // >= 1: override the number of segments a row is cut into
-    // Long rows are cut into nseg segments of seg_tiles tiles (16 tokens each), one
+    // Long rows are cut into nseg segments of seg_tiles forward tiles (kFwdTileTokens tokens each), one
     // block per (64 rows, segment).  carry: (nseg, B*D, N) states entering each
     // segment (read by the full pass; written by the summary pass as the states a
     // segment reaches from zero); dsum: (nseg, B*D) sum of time steps per segment.
