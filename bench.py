@@ -37,10 +37,11 @@ FWD_KEYS = ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")
 # same counter reads for a plain elementwise kernel that reads and writes 1 GiB
 # (bench.py --copy-calibration: FETCH_SIZE x2.0, WRITE_SIZE x1.0); profiles/ has the runs.
 MEASURED_TRAFFIC_BYTES = {
-    "vim_tiny": int((39360.4 * 2.0 + 31704.4) * 1024),
-    "vim_small": int((298360.4 * 2.0 + 125541.8) * 1024),
-    "hires_4096": int(((246061.6 + 106825.7 + 3498.6) * 2.0 + 56596.5 + 6528.6 + 6144.0) * 1024),
-    "wsi_bag": int(((162051.0 + 91369.3 + 3383.5) * 2.0 + 79656.1 + 6341.2 + 5968.0) * 1024),
+    "vim_tiny": int((42457.3 * 2.0 + 26023.4) * 1024),
+    "vim_small": int((236066.0 * 2.0 + 97180.0) * 1024),
+    # summary launch + carry chain + full pass
+    "hires_4096": int(((129130.2 + 76568.6 + 2356.6) * 2.0 + 59211.0 + 3265.0 + 3072.0) * 1024),
+    "wsi_bag": int(((116332.2 + 82080.3 + 12829.1) * 2.0 + 65553.0 + 3179.7 + 6078.9) * 1024),
 }
 
 
