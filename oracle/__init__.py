@@ -54,6 +54,10 @@ def _load():
         lib.lbscan_ref_bidir_fwd.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(_Problem), _dp]
         lib.lbscan_ref_bwd.restype = ctypes.c_int
         lib.lbscan_ref_bwd.argtypes = [ctypes.POINTER(_Problem)] + [_dp] * 9
+        lib.lbscan_ref_fwd_state.restype = ctypes.c_int
+        lib.lbscan_ref_fwd_state.argtypes = [ctypes.POINTER(_Problem), _dp, _dp, _dp]
+        lib.lbscan_ref_bwd_state.restype = ctypes.c_int
+        lib.lbscan_ref_bwd_state.argtypes = [ctypes.POINTER(_Problem)] + [_dp] * 12
         lib.lbscan_ref_num_threads.restype = ctypes.c_int
         lib.lbscan_ref_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -94,14 +98,25 @@ def _problem(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window, delta_softplus):
 
 
 def fwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, window,
-        delta_softplus=True):
-    """Locally bi-directional scan, forward.  Returns out (B,D,L) fp64."""
+        delta_softplus=True, h0=None, return_state=False):
+    """Locally bi-directional scan, forward.  Returns out (B,D,L) fp64, or
+    (out, hT) with return_state.  h0 (B,D,N): forward state entering at step 0."""
     p, keep = _problem(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window, delta_softplus)
     out = np.empty(keep[0].shape, dtype=np.float64)
-    rc = _load().lbscan_ref_fwd(ctypes.byref(p), _ptr(out))
+    if h0 is None and not return_state:
+        rc = _load().lbscan_ref_fwd(ctypes.byref(p), _ptr(out))
+        if rc:
+            raise RuntimeError(f"lbscan_ref_fwd failed: {rc}")
+        return out
+    Bsz, D, _ = keep[0].shape
+    N = keep[2].shape[1]
+    h0 = _f64(h0)
+    assert h0 is None or h0.shape == (Bsz, D, N)
+    hT = np.empty((Bsz, D, N), dtype=np.float64)
+    rc = _load().lbscan_ref_fwd_state(ctypes.byref(p), _ptr(h0), _ptr(out), _ptr(hT))
     if rc:
-        raise RuntimeError(f"lbscan_ref_fwd failed: {rc}")
-    return out
+        raise RuntimeError(f"lbscan_ref_fwd_state failed: {rc}")
+    return (out, hT) if return_state else out
 
 
 def bidir_fwd(set_f: dict, set_b: dict):
@@ -121,9 +136,10 @@ def bidir_fwd(set_f: dict, set_b: dict):
 
 
 def bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout, window,
-        delta_softplus=True):
+        delta_softplus=True, h0=None, dhT=None):
     """Gradients of fwd.  Returns a dict of fp64 arrays: dx, ddelta, dz (None
-    without a gate), dBm, dCm, dA, dDskip, ddelta_bias."""
+    without a gate), dBm, dCm, dA, dDskip, ddelta_bias; with h0 or dhT (the
+    gradient arriving at the final state) also dh0."""
     p, keep = _problem(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window, delta_softplus)
     xs = keep[0]
     Bsz, D, L = xs.shape
@@ -136,9 +152,21 @@ def bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout, windo
         "dBm": np.empty((Bsz, N, L)), "dCm": np.empty((Bsz, N, L)),
         "dA": np.empty((D, N)), "dDskip": np.empty((D,)), "ddelta_bias": np.empty((D,)),
     }
-    rc = _load().lbscan_ref_bwd(ctypes.byref(p), _ptr(dout), _ptr(g["dx"]), _ptr(g["ddelta"]),
-                                _ptr(g["dz"]), _ptr(g["dBm"]), _ptr(g["dCm"]), _ptr(g["dA"]),
-                                _ptr(g["dDskip"]), _ptr(g["ddelta_bias"]))
+    if h0 is None and dhT is None:
+        rc = _load().lbscan_ref_bwd(ctypes.byref(p), _ptr(dout), _ptr(g["dx"]), _ptr(g["ddelta"]),
+                                    _ptr(g["dz"]), _ptr(g["dBm"]), _ptr(g["dCm"]), _ptr(g["dA"]),
+                                    _ptr(g["dDskip"]), _ptr(g["ddelta_bias"]))
+        if rc:
+            raise RuntimeError(f"lbscan_ref_bwd failed: {rc}")
+        return g
+    h0, dhT = _f64(h0), _f64(dhT)
+    assert h0 is None or h0.shape == (Bsz, D, N)
+    assert dhT is None or dhT.shape == (Bsz, D, N)
+    g["dh0"] = np.empty((Bsz, D, N))
+    rc = _load().lbscan_ref_bwd_state(ctypes.byref(p), _ptr(h0), _ptr(dout), _ptr(dhT),
+                                      _ptr(g["dx"]), _ptr(g["ddelta"]), _ptr(g["dz"]),
+                                      _ptr(g["dBm"]), _ptr(g["dCm"]), _ptr(g["dA"]),
+                                      _ptr(g["dDskip"]), _ptr(g["ddelta_bias"]), _ptr(g["dh0"]))
     if rc:
-        raise RuntimeError(f"lbscan_ref_bwd failed: {rc}")
+        raise RuntimeError(f"lbscan_ref_bwd_state failed: {rc}")
     return g

@@ -12,9 +12,9 @@
  *                                additive Delta parameter, A-bar, B-bar)
  *   - global forward recurrence: Sec. 3.1, Eq. 1-2
  *   - local backward recurrence: Sec. 3.2, Eq. 7, in the order of Algorithm 1's
- *                                "locally backward recurrent" loop, including
- *                                its trick of carrying the backward state
- *                                without the current B-bar*x
+ *                                second (right-to-left) loop, including its
+ *                                trick of carrying the backward state without
+ *                                the current B-bar*x
  *   - combination and output:    Sec. 3.2, Eq. 8; gate: Algorithm 1 (SiLU(z))
  *   - global bi-directional scan (the comparison method): Sec. 3.1, Eq. 4-6
  *   - gradients: the paper gives no formulas (Appendix B reports only
@@ -33,12 +33,18 @@
  *   - the backward step multiplies by A-bar of the destination step
  *     (Algorithm 1 uses A-bar[:, i] on the state carried from i+1).
  *   - softplus(v) = v for v > 20 (relative effect < 3e-9), else log1p(exp(v)).
+ *   - Algorithm 1 starts both states at zero.  The *_state entry points also
+ *     accept a forward state h0 entering at the first step and return the
+ *     forward state hT after the last one (what a caller needs to process a
+ *     long sequence in chunks whose lengths are multiples of the window); the
+ *     local backward state stays zero at every window end, as in Eq. 7.
  *
  * Layout (all host, fp64, dense, last index contiguous):
  *   x, delta, z, out, dout, dx, ddelta, dz : (batch, dim, seqlen)
  *   Bm, Cm, dBm, dCm                        : (batch, dstate, seqlen)
  *   A, dA                                   : (dim, dstate)
  *   Dskip, delta_bias, dDskip, ddelta_bias  : (dim)
+ *   h0, hT, dh0, dhT                        : (batch, dim, dstate)
  *
  * Parity status: every function here is pinned by tests/test_oracle_pins.py
  * (brute-force sums, IIR-filter library routine, closed forms, impulse
@@ -111,11 +117,16 @@ static int check_problem(const lbref_problem *p)
  * with f the global forward state (Eq. 1) and g the local backward state
  * without the current input term (Eq. 7-8).
  */
-int lbscan_ref_fwd(const lbref_problem *p, double *out)
+int lbscan_ref_fwd_state(const lbref_problem *p, const double *h0, double *out, double *hT)
 {
     if (check_problem(p) || !out) return -1;
     const int Bsz = p->batch, D = p->dim, N = p->dstate, L = p->seqlen, M = p->window;
-    if ((long)Bsz * D * L == 0) return 0;
+    if ((long)Bsz * D * L == 0) {
+        /* no steps: the state passes through */
+        if (hT)
+            for (long i = 0; i < (long)Bsz * D * N; ++i) hT[i] = h0 ? h0[i] : 0.0;
+        return 0;
+    }
     int fail = 0;
 #pragma omp parallel for schedule(static)
     for (long row = 0; row < (long)Bsz * D; ++row) {
@@ -133,11 +144,12 @@ int lbscan_ref_fwd(const lbref_problem *p, double *out)
             const double *Bn = p->Bm + ((long)b * N + n) * L;
             const double *Cn = p->Cm + ((long)b * N + n) * L;
             /* global forward recurrence, Eq. 1 */
-            double hf = 0.0;
+            double hf = h0 ? h0[row * N + n] : 0.0;
             for (int t = 0; t < L; ++t) {
                 hf = exp(dt[t] * a) * hf + dt[t] * Bn[t] * xr[t];
                 F[t] = hf;
             }
+            if (hT) hT[row * N + n] = hf;
             /* local backward recurrence, Eq. 7, in Algorithm 1's order:
                decay (or reset at the last step of a window), use, then add
                the current input term for the next (earlier) step. */
@@ -156,6 +168,11 @@ int lbscan_ref_fwd(const lbref_problem *p, double *out)
         free(dt); free(F);
     }
     return fail ? -2 : 0;
+}
+
+int lbscan_ref_fwd(const lbref_problem *p, double *out)
+{
+    return lbscan_ref_fwd_state(p, NULL, out, NULL);
 }
 
 /*
@@ -230,12 +247,17 @@ int lbscan_ref_bidir_fwd(const lbref_problem *pf, const lbref_problem *pb, doubl
  *   dz_t    = dout_t y_t sigma(z_t) (1 + z_t (1 - sigma(z_t)))
  *   ddelta_t = ddt_t sigma(delta_t + bias) under softplus, else ddt_t;
  *   ddelta_bias = sum_{b,t} ddelta_t.
- * Every output is overwritten.  dz may be NULL iff p->z is NULL.
+ * With a state h0 entering (f_{-1} = h0) and the final state hT = f_{L-1}
+ * returned, the loss may also depend on hT: its gradient dhT joins phi at the
+ * last step (phi_{L-1} = e_{L-1} + dhT), and dh0 = abar_0 phi_0.
+ * Every output is overwritten.  dz may be NULL iff p->z is NULL; h0, dhT and
+ * dh0 may be NULL.
  */
-int lbscan_ref_bwd(const lbref_problem *p, const double *dout,
-                   double *dx, double *ddelta, double *dz,
-                   double *dBm, double *dCm,
-                   double *dA, double *dDskip, double *ddelta_bias)
+int lbscan_ref_bwd_state(const lbref_problem *p, const double *h0, const double *dout,
+                         const double *dhT,
+                         double *dx, double *ddelta, double *dz,
+                         double *dBm, double *dCm,
+                         double *dA, double *dDskip, double *ddelta_bias, double *dh0)
 {
     if (check_problem(p) || !dout || !dx || !ddelta || !dBm || !dCm || !dA ||
         !dDskip || !ddelta_bias) return -1;
@@ -246,7 +268,11 @@ int lbscan_ref_bwd(const lbref_problem *p, const double *dout,
     memset(dA, 0, sizeof(double) * (size_t)D * N);
     memset(dDskip, 0, sizeof(double) * (size_t)D);
     memset(ddelta_bias, 0, sizeof(double) * (size_t)D);
-    if ((long)Bsz * D * L == 0) return 0;
+    if ((long)Bsz * D * L == 0) {
+        if (dh0)
+            for (long i = 0; i < (long)Bsz * D * N; ++i) dh0[i] = dhT ? dhT[i] : 0.0;
+        return 0;
+    }
     int fail = 0;
     /* Rows of one batch entry share dBm/dCm; rows of one channel share
        dA/dDskip/ddelta_bias.  Loop batch entries in order and parallelise over
@@ -294,7 +320,8 @@ int lbscan_ref_bwd(const lbref_problem *p, const double *dout,
                     const double *Cn = p->Cm + ((long)b * N + n) * L;
                     double *aB = accB + (long)n * L, *aC = accC + (long)n * L;
                     /* recompute the forward quantities */
-                    double hf = 0.0;
+                    const double hin = h0 ? h0[row * N + n] : 0.0;
+                    double hf = hin;
                     for (int t = 0; t < L; ++t) {
                         ab[t] = exp(dt[t] * a);
                         u[t] = dt[t] * Bn[t] * xr[t];
@@ -314,9 +341,10 @@ int lbscan_ref_bwd(const lbref_problem *p, const double *dout,
                     }
                     /* adjoint of f: backward in time over the whole row */
                     double phi = 0.0, qsum = 0.0;
+                    const double dlast = dhT ? dhT[row * N + n] : 0.0;
                     for (int t = L - 1; t >= 0; --t) {
                         double e = dy[t] * Cn[t];
-                        phi = e + (t + 1 < L ? ab[t + 1] * phi : 0.0);
+                        phi = e + (t + 1 < L ? ab[t + 1] * phi : dlast);
                         double du = phi + (gam[t] - e);
                         double q = phi * (F[t] - u[t]) + gam[t] * G[t];
                         ddt[t] += q * a + du * Bn[t] * xr[t];
@@ -325,6 +353,7 @@ int lbscan_ref_bwd(const lbref_problem *p, const double *dout,
                         dx[row * L + t] += du * dt[t] * Bn[t];
                     }
                     dA[(long)d * N + n] += qsum;
+                    if (dh0) dh0[row * N + n] = ab[0] * phi;
                 }
                 for (int t = 0; t < L; ++t) {
                     double dd = p->delta_softplus ? ddt[t] * sigmoid64(draw[t] + bias) : ddt[t];
@@ -350,4 +379,13 @@ int lbscan_ref_bwd(const lbref_problem *p, const double *dout,
         }
     }
     return fail ? -2 : 0;
+}
+
+int lbscan_ref_bwd(const lbref_problem *p, const double *dout,
+                   double *dx, double *ddelta, double *dz,
+                   double *dBm, double *dCm,
+                   double *dA, double *dDskip, double *ddelta_bias)
+{
+    return lbscan_ref_bwd_state(p, NULL, dout, NULL, dx, ddelta, dz, dBm, dCm, dA, dDskip,
+                                ddelta_bias, NULL);
 }
