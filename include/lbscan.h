@@ -9,7 +9,7 @@
  *     dt_t   = softplus?(delta[b,d,t] + delta_bias[d])
  *     abar_t = exp(dt_t * A[d,n])           u_t = dt_t * Bm[b,n,t] * x[b,d,t]
  * the library computes
- *     f_t = abar_t f_{t-1} + u_t,  f_{-1} = 0           global forward scan (Eq. 1)
+ *     f_t = abar_t f_{t-1} + u_t,  f_{-1} = h0 or 0     global forward scan (Eq. 1)
  *     g_t = 0 at the last step of each window [kM, kM+M-1] (and at t = L-1),
  *           abar_t (g_{t+1} + u_{t+1}) otherwise        local backward scan (Eq. 7,
  *           without its own input term: the "B x" counted once, Eq. 8)
@@ -21,6 +21,7 @@
  *     Bm, Cm, dBm, dCm                     : (B, N, L)     element type = dtype
  *     A, dA                                : (D, N)        fp32
  *     Dskip, delta_bias and their grads    : (D)           fp32
+ *     h0, hT, dh0, dhT                     : (B, D, N)     fp32
  * One B/C group is shared by all channels (Algorithm 1: B, C have shape
  * (B, L, N)); A is real.
  *
@@ -82,6 +83,13 @@ typedef struct lbscan_args {
                                  for these shapes); lbscan_bwd given the same buffer starts
                                  from them instead of recomputing them.  NULL: not used. */
     size_t       saved_state_bytes;
+    /* Forward state entering and leaving the call, for sequences processed in
+       chunks (Algorithm 1 starts from zero: both NULL).  The local backward state
+       never crosses a call, so chunk lengths must be multiples of the window for
+       the chunks to add up to the whole sequence.  With reverse = 1 the state
+       enters at t = L-1 and leaves after t = 0.  Not used by lbscan_bidir_fwd. */
+    const float *h0;          /* (B,D,N) or NULL: zeros */
+    float       *hT;          /* (B,D,N) out of lbscan_fwd, or NULL: not wanted */
 } lbscan_args;
 
 #define LBSCAN_WS_FWD   0
@@ -105,6 +113,16 @@ int lbscan_bwd(const lbscan_args *fwd_args, const void *dout,
                void *dBm, void *dCm,
                float *dA, float *dDskip, float *ddelta_bias,
                void *hip_stream);
+
+/* lbscan_bwd for chunked sequences: dhT (B,D,N) fp32, nullable, is the gradient
+ * arriving at the state that left the forward call (fwd_args->hT); dh0 (B,D,N)
+ * fp32, nullable, receives the gradient with respect to fwd_args->h0 (it is
+ * defined, and written, also when h0 is NULL).  fwd_args->hT is not read. */
+int lbscan_bwd_state(const lbscan_args *fwd_args, const void *dout, const float *dhT,
+                     void *dx, void *ddelta, void *dz,
+                     void *dBm, void *dCm,
+                     float *dA, float *dDskip, float *ddelta_bias, float *dh0,
+                     void *hip_stream);
 
 /* The comparison method: global bi-directional scan (Sec. 3.1, Eq. 4-6) as two
  * full passes over HBM.  Pass 1 scans fwd_set left to right (Eq. 1-2); pass 2

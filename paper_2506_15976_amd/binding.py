@@ -20,7 +20,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 EXPORTS = (
     "lbscan_fwd", "lbscan_bwd", "lbscan_bidir_fwd", "lbscan_workspace_bytes",
     "lbscan_default_window", "lbscan_strerror", "lbscan_last_error", "lbscan_version",
-    "lbscan_set_option",
+    "lbscan_set_option", "lbscan_bwd_state",
 )
 
 
@@ -35,6 +35,7 @@ class LbscanArgs(ctypes.Structure):
         ("Dskip", ctypes.c_void_p), ("delta_bias", ctypes.c_void_p), ("y", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("saved_state", ctypes.c_void_p), ("saved_state_bytes", ctypes.c_size_t),
+        ("h0", ctypes.c_void_p), ("hT", ctypes.c_void_p),
     ]
 
 
@@ -67,6 +68,8 @@ def load():
     lib.lbscan_bidir_fwd.argtypes = [ap, ap, vp]
     lib.lbscan_bwd.restype = ctypes.c_int
     lib.lbscan_bwd.argtypes = [ap] + [vp] * 10
+    lib.lbscan_bwd_state.restype = ctypes.c_int
+    lib.lbscan_bwd_state.argtypes = [ap] + [vp] * 12
     lib.lbscan_workspace_bytes.restype = ctypes.c_size_t
     lib.lbscan_workspace_bytes.argtypes = [ap, ctypes.c_int]
     lib.lbscan_default_window.restype = ctypes.c_int
@@ -110,9 +113,11 @@ def _stream(stream):
 
 
 def make_args(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, window,
-              delta_softplus=True, reverse=False, y=None, workspace=None, saved_state=None):
+              delta_softplus=True, reverse=False, y=None, workspace=None, saved_state=None,
+              h0=None, hT=None):
     """Fill a struct lbscan_args from device tensors.  Shapes: x, delta, z, y
-    (B,D,L); Bm, Cm (B,N,L); A (D,N) fp32; Dskip, delta_bias (D) fp32."""
+    (B,D,L); Bm, Cm (B,N,L); A (D,N) fp32; Dskip, delta_bias (D) fp32; h0, hT
+    (B,D,N) fp32."""
     import torch
     Bsz, D, L = x.shape
     N = A.shape[1]
@@ -123,14 +128,15 @@ def make_args(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, windo
             continue
         if tuple(t.shape) != shape or t.dtype != x.dtype:
             raise LbscanError(EINVAL, f"{name}: expected {shape} {x.dtype}, got {tuple(t.shape)} {t.dtype}")
-    for name, t, shape in (("A", A, (D, N)), ("Dskip", Dskip, (D,)), ("delta_bias", delta_bias, (D,))):
+    for name, t, shape in (("A", A, (D, N)), ("Dskip", Dskip, (D,)), ("delta_bias", delta_bias, (D,)),
+                           ("h0", h0, (Bsz, D, N)), ("hT", hT, (Bsz, D, N))):
         if t is None:
             continue
         if tuple(t.shape) != shape or t.dtype != torch.float32:
             raise LbscanError(EINVAL, f"{name}: expected {shape} float32")
     for name, t in (("x", x), ("delta", delta), ("A", A), ("Bm", Bm), ("Cm", Cm), ("Dskip", Dskip),
                     ("z", z), ("delta_bias", delta_bias), ("y", y), ("workspace", workspace),
-                    ("saved_state", saved_state)):
+                    ("saved_state", saved_state), ("h0", h0), ("hT", hT)):
         if t is not None and (not t.is_cuda or not t.is_contiguous()):
             raise LbscanError(EINVAL, f"{name} must be a contiguous device tensor")
     a = LbscanArgs(Bsz, D, N, L, int(window), code, int(bool(delta_softplus)), int(bool(reverse)),
@@ -138,7 +144,8 @@ def make_args(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, windo
                    _ptr(delta_bias), _ptr(y), _ptr(workspace),
                    0 if workspace is None else workspace.numel() * workspace.element_size(),
                    _ptr(saved_state),
-                   0 if saved_state is None else saved_state.numel() * saved_state.element_size())
+                   0 if saved_state is None else saved_state.numel() * saved_state.element_size(),
+                   _ptr(h0), _ptr(hT))
     return a
 
 
@@ -179,16 +186,23 @@ def lbscan_saved_state(x, A, *, window):
 
 
 def lbscan_fwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, window,
-               delta_softplus=True, reverse=False, out=None, stream=None, saved_state=None):
-    """out = locally bi-directional scan of the inputs (see include/lbscan.h)."""
+               delta_softplus=True, reverse=False, out=None, stream=None, saved_state=None,
+               h0=None, return_state=False):
+    """out = locally bi-directional scan of the inputs (see include/lbscan.h).
+    h0 (B,D,N) fp32: forward state entering the call; with return_state the result
+    is (out, hT), hT the state that leaves it."""
     import torch
     y = torch.empty_like(x) if out is None else out
+    hT = None
+    if return_state:
+        hT = torch.empty((x.shape[0], x.shape[1], A.shape[1]), dtype=torch.float32, device=x.device)
     a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
-                  delta_softplus=delta_softplus, reverse=reverse, y=y, saved_state=saved_state)
+                  delta_softplus=delta_softplus, reverse=reverse, y=y, saved_state=saved_state,
+                  h0=h0, hT=hT)
     ws = _workspace_for(a, WS_FWD, x)
     _check(load().lbscan_fwd(ctypes.byref(a), _stream(stream)), "lbscan_fwd")
     del ws
-    return y
+    return (y, hT) if return_state else y
 
 
 def lbscan_bidir_fwd(set_f: dict, set_b: dict, *, out=None, stream=None):
@@ -211,12 +225,15 @@ def lbscan_bidir_fwd(set_f: dict, set_b: dict, *, out=None, stream=None):
 
 
 def lbscan_bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout, window,
-               delta_softplus=True, reverse=False, stream=None, saved_state=None):
+               delta_softplus=True, reverse=False, stream=None, saved_state=None,
+               h0=None, dhT=None):
     """Gradients of lbscan_fwd.  Returns a dict: dx, ddelta, dz, dBm, dCm, dA,
-    dDskip, ddelta_bias (None where the input is absent)."""
+    dDskip, ddelta_bias (None where the input is absent); with h0 or dhT (the
+    gradient arriving at the state that left the forward call) also dh0, through
+    lbscan_bwd_state."""
     import torch
     a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
-                  delta_softplus=delta_softplus, reverse=reverse, saved_state=saved_state)
+                  delta_softplus=delta_softplus, reverse=reverse, saved_state=saved_state, h0=h0)
     if tuple(dout.shape) != tuple(x.shape) or dout.dtype != x.dtype or not dout.is_contiguous():
         raise LbscanError(EINVAL, "dout must match x")
     g = dict(
@@ -228,9 +245,21 @@ def lbscan_bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout
         ddelta_bias=torch.empty_like(delta_bias) if delta_bias is not None else None,
     )
     ws = _workspace_for(a, WS_BWD, x)
-    rc = load().lbscan_bwd(ctypes.byref(a), _ptr(dout), _ptr(g["dx"]), _ptr(g["ddelta"]),
-                           _ptr(g["dz"]), _ptr(g["dBm"]), _ptr(g["dCm"]), _ptr(g["dA"]),
-                           _ptr(g["dDskip"]), _ptr(g["ddelta_bias"]), _stream(stream))
-    _check(rc, "lbscan_bwd")
+    if h0 is None and dhT is None:
+        rc = load().lbscan_bwd(ctypes.byref(a), _ptr(dout), _ptr(g["dx"]), _ptr(g["ddelta"]),
+                               _ptr(g["dz"]), _ptr(g["dBm"]), _ptr(g["dCm"]), _ptr(g["dA"]),
+                               _ptr(g["dDskip"]), _ptr(g["ddelta_bias"]), _stream(stream))
+        _check(rc, "lbscan_bwd")
+    else:
+        shape = (x.shape[0], x.shape[1], A.shape[1])
+        if dhT is not None and (tuple(dhT.shape) != shape or dhT.dtype != torch.float32
+                                or not dhT.is_cuda or not dhT.is_contiguous()):
+            raise LbscanError(EINVAL, f"dhT must be a contiguous float32 device tensor of shape {shape}")
+        g["dh0"] = torch.empty(shape, dtype=torch.float32, device=x.device)
+        rc = load().lbscan_bwd_state(ctypes.byref(a), _ptr(dout), _ptr(dhT), _ptr(g["dx"]),
+                                     _ptr(g["ddelta"]), _ptr(g["dz"]), _ptr(g["dBm"]), _ptr(g["dCm"]),
+                                     _ptr(g["dA"]), _ptr(g["dDskip"]), _ptr(g["ddelta_bias"]),
+                                     _ptr(g["dh0"]), _stream(stream))
+        _check(rc, "lbscan_bwd_state")
     del ws
     return g

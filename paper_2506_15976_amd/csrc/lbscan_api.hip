@@ -49,7 +49,8 @@ int check_args(const lbscan_args* a, bool need_y, bool* empty)
     if (rc != LBSCAN_OK || *empty) return rc;
     if (!a->x || !a->delta || (need_y && !a->y)) return LBSCAN_EINVAL;
     if (a->dstate > 0 && (!a->A || !a->Bm || !a->Cm)) return LBSCAN_EINVAL;
-    const void* ptrs[] = {a->x, a->delta, a->Bm, a->Cm, a->z, a->A, a->Dskip, a->delta_bias, a->y};
+    const void* ptrs[] = {a->x, a->delta, a->Bm, a->Cm, a->z, a->A, a->Dskip, a->delta_bias, a->y,
+                          a->h0, a->hT};
     for (const void* p : ptrs)
         if (p && !aligned4(p)) return LBSCAN_EINVAL;
     return LBSCAN_OK;
@@ -80,6 +81,7 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     p.force_nseg = tuning_nseg();
     p.nseg = 1; p.seg_tiles = 0; p.summary_only = 0; p.carry = nullptr; p.dsum = nullptr;
     p.ckpt = nullptr; p.cum = nullptr; p.dout = nullptr; p.psi = nullptr;
+    p.h0 = a->h0; p.hT = a->hT;
     return p;
 }
 
@@ -91,7 +93,15 @@ int lbscan_fwd(const lbscan_args* args, void* hip_stream)
 {
     bool empty;
     int rc = check_args(args, true, &empty);
-    if (rc != LBSCAN_OK || empty) return rc;
+    if (rc != LBSCAN_OK) return rc;
+    if (empty) {
+        // no steps: the state passes through
+        if (!args->hT) return LBSCAN_OK;
+        if ((args->h0 && !aligned4(args->h0)) || !aligned4(args->hT)) return LBSCAN_EINVAL;
+        hipError_t e = lbscan::launch_copy(args->hT, args->h0, (long)args->batch * args->dim * args->dstate,
+                                           static_cast<hipStream_t>(hip_stream));
+        return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_fwd");
+    }
     const int M = effective_window(args->window, args->seqlen);
     if (M == 0) return LBSCAN_EUNSUPPORTED;
     lbscan::FwdParams p = to_params(args, M);
@@ -117,6 +127,7 @@ int lbscan_bidir_fwd(const lbscan_args* fs, const lbscan_args* bs, void* hip_str
     if (rc != LBSCAN_OK) return rc;
     if (fs->batch != bs->batch || fs->dim != bs->dim || fs->dstate != bs->dstate ||
         fs->seqlen != bs->seqlen || fs->dtype != bs->dtype) return LBSCAN_EINVAL;
+    if (fs->h0 || fs->hT || bs->h0 || bs->hT) return LBSCAN_EINVAL;   // whole sequences only
     if (empty_f) return LBSCAN_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
@@ -150,6 +161,14 @@ int lbscan_bwd(const lbscan_args* a, const void* dout,
                void* dx, void* ddelta, void* dz, void* dBm, void* dCm,
                float* dA, float* dDskip, float* ddelta_bias, void* hip_stream)
 {
+    return lbscan_bwd_state(a, dout, nullptr, dx, ddelta, dz, dBm, dCm, dA, dDskip, ddelta_bias,
+                            nullptr, hip_stream);
+}
+
+int lbscan_bwd_state(const lbscan_args* a, const void* dout, const float* dhT,
+                     void* dx, void* ddelta, void* dz, void* dBm, void* dCm,
+                     float* dA, float* dDskip, float* ddelta_bias, float* dh0, void* hip_stream)
+{
     bool empty;
     int rc = check_args(a, false, &empty);
     if (rc != LBSCAN_OK) return rc;
@@ -164,10 +183,13 @@ int lbscan_bwd(const lbscan_args* a, const void* dout,
         hipError_t e = lbscan::launch_zero(dA, (long)a->dim * a->dstate, s);
         if (e == hipSuccess) e = lbscan::launch_zero(dDskip, a->dim, s);
         if (e == hipSuccess) e = lbscan::launch_zero(ddelta_bias, a->dim, s);
+        // no steps: the gradient of the leaving state is that of the entering state
+        if (e == hipSuccess && dh0 && aligned4(dh0) && (!dhT || aligned4(dhT)))
+            e = lbscan::launch_copy(dh0, dhT, (long)a->batch * a->dim * a->dstate, s);
         return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bwd");
     }
     if (!dout || !dx || !ddelta || (a->z && !dz)) return LBSCAN_EINVAL;
-    const void* ptrs[] = {dout, dx, ddelta, dz, dBm, dCm, dA, dDskip, ddelta_bias};
+    const void* ptrs[] = {dout, dx, ddelta, dz, dBm, dCm, dA, dDskip, ddelta_bias, dhT, dh0};
     for (const void* q : ptrs)
         if (q && !aligned4(q)) return LBSCAN_EINVAL;
     const int M = effective_window(a->window, a->seqlen);
@@ -185,13 +207,15 @@ int lbscan_bwd(const lbscan_args* a, const void* dout,
     p.dBacc = nullptr; p.dCacc = nullptr;
     p.dA = dA; p.dDskip = a->Dskip ? dDskip : nullptr; p.dbias = a->delta_bias ? ddelta_bias : nullptr;
     p.ckpt = nullptr; p.nseg = 1; p.seg_tiles = 0; p.cum = nullptr; p.carry = nullptr; p.psi_in = nullptr;
+    p.dh0 = dh0;
+    f.hT = nullptr;
     const float* saved = nullptr;
     if (a->saved_state) {
         const size_t sneed = lbscan::saved_state_bytes(f);
         if (sneed && (a->saved_state_bytes < sneed || !aligned4(a->saved_state))) return LBSCAN_EWORKSPACE;
         if (sneed) saved = static_cast<const float*>(a->saved_state);
     }
-    hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, saved, s);
+    hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, saved, dhT, s);
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bwd");
 }
 

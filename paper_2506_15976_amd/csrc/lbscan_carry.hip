@@ -21,8 +21,8 @@ namespace {
 
 __global__ void __launch_bounds__(256)
 carry_chain_kernel(float* __restrict__ carry, const float* __restrict__ dsum,
-                   const float* __restrict__ A, int rows, int D, int N, int nseg, int reverse,
-                   int G)
+                   const float* __restrict__ A, const float* __restrict__ init,
+                   int rows, int D, int N, int nseg, int reverse, int G)
 {
     const long npairs = (long)rows * N;
     const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -32,7 +32,7 @@ carry_chain_kernel(float* __restrict__ carry, const float* __restrict__ dsum,
     const long i = valid ? pair : npairs - 1;         // clamped: every lane shuffles
     const int row = (int)(i / N), n = (int)(i % N);
     const float a2 = A[(long)(row % D) * N + n] * kLog2e;
-    float cin = 0.0f;                                 // state entering the chunk
+    float cin = init ? init[i] : 0.0f;                // state entering the chunk
     for (int base = 0; base < nseg; base += G) {
         const int ss = base + g;
         const bool on = ss < nseg;
@@ -60,6 +60,13 @@ __global__ void __launch_bounds__(256) zero_kernel(float* __restrict__ dst, long
     if (i < n) dst[i] = 0.0f;
 }
 
+__global__ void __launch_bounds__(256)
+copy_kernel(float* __restrict__ dst, const float* __restrict__ src, long n)
+{
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
 // lanes per (row, n) pair: the smallest power of two that covers the chain, one
 // wave at most
 int chain_group(int nseg)
@@ -78,6 +85,14 @@ hipError_t launch_zero(float* dst, long n, hipStream_t stream)
     return hipGetLastError();
 }
 
+hipError_t launch_copy(float* dst, const float* src, long n, hipStream_t stream)
+{
+    if (!src) return launch_zero(dst, n, stream);
+    if (n <= 0 || !dst) return hipSuccess;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, dst, src, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_carry_chain(const FwdParams& p, hipStream_t stream)
 {
     const int rows = p.batch * p.dim;
@@ -86,11 +101,12 @@ hipError_t launch_carry_chain(const FwdParams& p, hipStream_t stream)
     const int G = chain_group(p.nseg);
     const unsigned blocks = (unsigned)((n * G + 255) / 256);
     hipLaunchKernelGGL(carry_chain_kernel, dim3(blocks), dim3(256), 0, stream,
-                       p.carry, p.dsum, p.A, rows, p.dim, p.dstate, p.nseg, 0, G);
+                       p.carry, p.dsum, p.A, p.h0, rows, p.dim, p.dstate, p.nseg, 0, G);
     return hipGetLastError();
 }
 
-hipError_t launch_carry_chain_reverse(const FwdParams& p, float* buf, hipStream_t stream)
+hipError_t launch_carry_chain_reverse(const FwdParams& p, float* buf, const float* init,
+                                      hipStream_t stream)
 {
     const int rows = p.batch * p.dim;
     const long n = (long)rows * p.dstate;
@@ -98,7 +114,7 @@ hipError_t launch_carry_chain_reverse(const FwdParams& p, float* buf, hipStream_
     const int G = chain_group(p.nseg);
     const unsigned blocks = (unsigned)((n * G + 255) / 256);
     hipLaunchKernelGGL(carry_chain_kernel, dim3(blocks), dim3(256), 0, stream,
-                       buf, p.dsum, p.A, rows, p.dim, p.dstate, p.nseg, 1, G);
+                       buf, p.dsum, p.A, init, rows, p.dim, p.dstate, p.nseg, 1, G);
     return hipGetLastError();
 }
 

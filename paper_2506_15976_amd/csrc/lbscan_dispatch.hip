@@ -78,7 +78,8 @@ hipError_t launch_fwd(FwdParams p, void* workspace, float* saved, hipStream_t st
     p.nseg = s.nseg;
     p.seg_tiles = s.seg_tiles;
     p.summary_only = 0;
-    p.carry = nullptr;
+    // uncut rows: the entering state is the (only) carried-in state
+    p.carry = const_cast<float*>(p.h0);
     p.dsum = nullptr;
     if (s.nseg > 1) {
         if (!workspace) return hipErrorInvalidValue;
@@ -133,7 +134,7 @@ size_t bwd_workspace_bytes(const FwdParams& f)
 }
 
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
-                      const float* saved, hipStream_t stream)
+                      const float* saved, const float* dhT, hipStream_t stream)
 {
     if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return hipSuccess;
     if (!workspace) return hipErrorInvalidValue;
@@ -147,8 +148,10 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
     p.cum = ws + l.cum;
     p.nseg = s.nseg;
     p.seg_tiles = s.seg_tiles * (kFwdTileTokens / kTileTokens);
-    p.carry = s.nseg > 1 ? ws + l.carry : nullptr;
-    p.psi_in = s.nseg > 1 ? ws + l.psi : nullptr;
+    // uncut rows: the entering state and the gradient arriving at the leaving state
+    // take the places of the chained values
+    p.carry = s.nseg > 1 ? ws + l.carry : f.h0;
+    p.psi_in = s.nseg > 1 ? ws + l.psi : dhT;
 
     hipError_t e;
     if ((e = launch_zero(p.dBacc, bnl, stream)) != hipSuccess) return e;
@@ -158,9 +161,10 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
     if ((e = launch_zero(p.dbias, f.dim, stream)) != hipSuccess) return e;
 
     if (saved && s.nseg == 1) {
-        // the forward call left the checkpoints: no summary pass
+        // the forward call left the checkpoints (entering state included): no summary pass
         p.ckpt = saved;
         p.cum = nullptr;
+        p.carry = nullptr;
         e = f.dtype == 0 ? launch_bwd_rowlane_f32(p, stream) : launch_bwd_rowlane_bf16(p, stream);
         if (e != hipSuccess) return e;
         if (f.dtype != 0) {
@@ -188,7 +192,7 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
     if (e != hipSuccess) return e;
     if (s.nseg > 1) {
         if ((e = launch_carry_chain(q, stream)) != hipSuccess) return e;
-        if ((e = launch_carry_chain_reverse(q, q.psi, stream)) != hipSuccess) return e;
+        if ((e = launch_carry_chain_reverse(q, q.psi, dhT, stream)) != hipSuccess) return e;
     }
 
     e = f.dtype == 0 ? launch_bwd_rowlane_f32(p, stream) : launch_bwd_rowlane_bf16(p, stream);

@@ -43,6 +43,9 @@ struct FwdParams {
     // psi (nseg, B*D, N) out: the segment's summary of the right-to-left recurrence
     const void* dout;
     float* psi;
+    // forward state entering the row (nullable: zeros) and leaving it (nullable), (B*D, N)
+    const float* h0;
+    float* hT;
 };
 
 // Arguments of one backward launch: the forward inputs plus the gradient tensors.
@@ -76,6 +79,7 @@ struct BwdParams {
     const float* cum;     // (ntiles, B*D): time-step sum from the segment start to the tile
     const float* carry;   // (nseg, B*D, N): forward state entering each segment (null: zeros)
     const float* psi_in;  // (nseg, B*D, N): psi entering each segment from the right
+    float* dh0;           // (B*D, N), nullable: psi leaving the row on the left
 };
 
 constexpr int kTileTokens = 16;      // tokens per tile of the backward kernel = checkpoint spacing
@@ -113,14 +117,20 @@ hipError_t launch_zero(float* dst, long n, hipStream_t stream);
 // conversion of dBm / dCm when the storage type is not fp32.  dBm / dCm are the
 // caller's outputs; workspace must hold bwd_workspace_bytes(f) bytes.
 // saved (nullable): checkpoints left by launch_fwd on the same inputs.
+// dhT (nullable): gradient arriving at the state that leaves the row.
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
-                      const float* saved, hipStream_t stream);
+                      const float* saved, const float* dhT, hipStream_t stream);
 size_t bwd_workspace_bytes(const FwdParams& f);
 
 // Chains the per-segment summaries into the states entering each segment
-// (lbscan_carry.hip): carry[s] <- exclusive scan over s of (exp(A*dsum), carry).
+// (lbscan_carry.hip): carry[s] <- exclusive scan over s of (exp(A*dsum), carry),
+// started from p.h0 (zeros when null).
 hipError_t launch_carry_chain(const FwdParams& p, hipStream_t stream);
-// The same chain over `buf` (nseg, B*D, N) walking the segments right to left.
-hipError_t launch_carry_chain_reverse(const FwdParams& p, float* buf, hipStream_t stream);
+// The same chain over `buf` (nseg, B*D, N) walking the segments right to left,
+// started from init (B*D, N), zeros when null.
+hipError_t launch_carry_chain_reverse(const FwdParams& p, float* buf, const float* init,
+                                      hipStream_t stream);
+// dst[i] = src[i] (zeros when src is null), n floats.
+hipError_t launch_copy(float* dst, const float* src, long n, hipStream_t stream);
 
 }  // namespace lbscan

@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_struct_layout_matches_header():
     from paper_2506_15976_amd.binding import LbscanArgs
     # 8 int32 + 9 pointers + (workspace pointer, size_t) + (saved_state pointer, size_t)
-    assert ctypes.sizeof(LbscanArgs) == 8 * 4 + 10 * 8 + 8 + 16
+    assert ctypes.sizeof(LbscanArgs) == 8 * 4 + 10 * 8 + 8 + 16 + 16
     assert LbscanArgs.x.offset == 32
     assert LbscanArgs.workspace_bytes.offset == 32 + 10 * 8
     assert LbscanArgs.saved_state.offset == 32 + 11 * 8
