@@ -82,6 +82,7 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     p.nseg = 1; p.seg_tiles = 0; p.summary_only = 0; p.carry = nullptr; p.dsum = nullptr;
     p.ckpt = nullptr; p.cum = nullptr; p.dout = nullptr; p.psi = nullptr;
     p.h0 = a->h0; p.hT = a->hT;
+    p.generic_window = 0; p.seg_tokens = 0;
     return p;
 }
 
@@ -103,7 +104,15 @@ int lbscan_fwd(const lbscan_args* args, void* hip_stream)
         return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_fwd");
     }
     const int M = effective_window(args->window, args->seqlen);
-    if (M == 0) return LBSCAN_EUNSUPPORTED;
+    if (M == 0) {
+        // no compiled kernel for this window length: the two-launch path
+        lbscan::FwdParams p = to_params(args, args->window < args->seqlen ? args->window : args->seqlen);
+        const size_t need = lbscan::fwd_generic_workspace_bytes(p);
+        if (need && (!args->workspace || args->workspace_bytes < need || !aligned4(args->workspace)))
+            return LBSCAN_EWORKSPACE;
+        hipError_t e = lbscan::launch_fwd_generic(p, args->workspace, static_cast<hipStream_t>(hip_stream));
+        return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_fwd");
+    }
     lbscan::FwdParams p = to_params(args, M);
     const size_t need = lbscan::fwd_workspace_bytes(p);
     if (need && (!args->workspace || args->workspace_bytes < need || !aligned4(args->workspace)))
@@ -225,7 +234,13 @@ size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
     if (check_args_sizes(a, &empty) != LBSCAN_OK || empty) return 0;
     const size_t bdl = (size_t)a->batch * a->dim * a->seqlen;
     int M = effective_window(a->window, a->seqlen);
-    if (M == 0) M = 1;
+    if (M == 0) {
+        // forward only, as two launches; there is no backward pass for this window length
+        if (which == LBSCAN_WS_FWD)
+            return lbscan::fwd_generic_workspace_bytes(to_params(a, a->window < a->seqlen ? a->window : a->seqlen));
+        if (which != LBSCAN_WS_BIDIR) return 0;
+        M = 1;
+    }
     switch (which) {
         case LBSCAN_WS_FWD:
             return lbscan::fwd_workspace_bytes(to_params(a, M));

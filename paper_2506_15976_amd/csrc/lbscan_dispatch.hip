@@ -95,6 +95,58 @@ hipError_t launch_fwd(FwdParams p, void* workspace, float* saved, hipStream_t st
     return launch(p);
 }
 
+// ---- window lengths without a compiled kernel ---------------------------------
+//
+// Eq. 8 splits into the plain forward scan (sum_n Cm f + Dskip x: the kernel
+// compiled for window 1, entering and leaving states included) and the local
+// backward part sum_n Cm g, which never crosses a window end.  Pass 1 leaves the
+// first in fp32 (in y itself when y is fp32, else at the start of the
+// workspace); pass 2 adds the second for any window length, gates and writes y.
+
+size_t fwd_generic_workspace_bytes(const FwdParams& p)
+{
+    if (p.batch == 0 || p.dim == 0 || p.seqlen == 0) return 0;
+    FwdParams p1 = p;
+    p1.window = 1;
+    const size_t partial = p.dtype == 0 ? 0 : (size_t)p.batch * p.dim * p.seqlen * sizeof(float);
+    return partial + fwd_workspace_bytes(p1);
+}
+
+hipError_t launch_fwd_generic(FwdParams p, void* workspace, hipStream_t stream)
+{
+    if (p.batch == 0 || p.dim == 0 || p.seqlen == 0) return hipSuccess;
+    float* partial = static_cast<float*>(p.y);
+    char* scratch = static_cast<char*>(workspace);
+    if (p.dtype != 0) {
+        if (!workspace) return hipErrorInvalidValue;
+        partial = static_cast<float*>(workspace);
+        scratch += (size_t)p.batch * p.dim * p.seqlen * sizeof(float);
+    }
+    FwdParams p1 = p;
+    p1.window = 1; p1.z = nullptr; p1.y = partial; p1.y_is_f32 = 1;
+    hipError_t e = launch_fwd(p1, scratch, nullptr, stream);
+    if (e != hipSuccess) return e;
+
+    FwdParams p2 = p;
+    p2.generic_window = 1; p2.Dskip = nullptr; p2.yprev = partial;
+    p2.h0 = nullptr; p2.hT = nullptr; p2.carry = nullptr; p2.dsum = nullptr;
+    p2.ckpt = nullptr; p2.cum = nullptr; p2.summary_only = 0; p2.seg_tiles = 0;
+    // segments of whole windows, at least 64 steps each, enough of them to fill the chip
+    const long nrb = (long)((p.dim + 63) / 64) * p.batch;
+    const long M = p.window, L = p.seqlen;
+    const long nw = (L + M - 1) / M;
+    long want_seg = nrb < 768 ? (768 + nrb - 1) / nrb : 1;
+    if (p.force_nseg >= 1) want_seg = p.force_nseg;
+    long wps = (nw + want_seg - 1) / want_seg;
+    if (p.force_nseg < 1 && wps * M < 64) wps = (64 + M - 1) / M;
+    if (wps < 1) wps = 1;
+    p2.seg_tokens = (int)(wps * M);
+    p2.nseg = (int)((L + p2.seg_tokens - 1) / p2.seg_tokens);
+    const int wl = pick_shape(p).waves_log2;
+    return p2.dtype == 0 ? launch_fwd_rowlane_f32(p2, wl, stream)
+                         : launch_fwd_rowlane_bf16(p2, wl, stream);
+}
+
 // ---- backward ----------------------------------------------------------------
 
 namespace {

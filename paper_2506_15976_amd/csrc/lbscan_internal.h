@@ -46,6 +46,11 @@ struct FwdParams {
     // forward state entering the row (nullable: zeros) and leaving it (nullable), (B*D, N)
     const float* h0;
     float* hT;
+    // second pass of the path for window lengths without a compiled kernel: only
+    // the local backward part, added to yprev; window is then the run-time window
+    // length and the grid has one block per (64 rows, seg_tokens logical steps)
+    int generic_window;
+    int seg_tokens;
 };
 
 // Arguments of one backward launch: the forward inputs plus the gradient tensors.
@@ -100,6 +105,10 @@ hipError_t launch_fwd_rowlane_bf16(const FwdParams& p, int waves_log2, hipStream
 // a backward call (ignored when that size is 0).
 hipError_t launch_fwd(FwdParams p, void* workspace, float* saved, hipStream_t stream);
 size_t fwd_workspace_bytes(const FwdParams& p);
+// The same for a window length without a compiled kernel (p.window <= p.seqlen, any
+// value): two launches, the plain forward scan and the local backward part.
+hipError_t launch_fwd_generic(FwdParams p, void* workspace, hipStream_t stream);
+size_t fwd_generic_workspace_bytes(const FwdParams& p);
 // Bytes of the saved-state buffer, 0 when rows are cut into segments (the backward
 // pass then needs its own summary pass anyway).
 size_t saved_state_bytes(const FwdParams& p);

@@ -66,7 +66,9 @@ def test_validation_without_gpu(lib):
     a.seqlen = 64
     a.window = 3
     a.x = a.delta = a.y = a.A = a.Bm = a.Cm = 256                   # never dereferenced on the host
-    assert lib.lbscan_fwd(ctypes.byref(a), None) == EUNSUPPORTED    # window not compiled
+    # a window length without a fused kernel has a forward path (two passes) but no backward pass
+    fake = ctypes.c_void_p(256)
+    assert lib.lbscan_bwd(ctypes.byref(a), *([fake] * 9), None) == EUNSUPPORTED
     a.x = 257
     a.window = 4
     assert lib.lbscan_fwd(ctypes.byref(a), None) == EINVAL          # misaligned pointer

@@ -133,13 +133,62 @@ def test_window_covering_short_row(lb, oracle):
     _run_fwd(lb, oracle, s, window=1000)
 
 
-def test_unsupported_window_is_an_error(lb):
+def test_backward_of_a_window_without_fused_kernel_is_an_error(lb):
     from gpu_util import fwd_inputs, to_device
     from paper_2506_15976_amd.inputs import make_inputs
-    dev = to_device(make_inputs(1, 64, 16, 64, seed=6), "fp32")
+    dev = to_device(make_inputs(1, 64, 16, 64, seed=6, with_dout=True), "fp32")
     with pytest.raises(lb.LbscanError) as ei:
-        lb.lbscan_fwd(**fwd_inputs(dev), window=3)
+        lb.lbscan_bwd(**fwd_inputs(dev), dout=dev["dout"], window=3)
     assert ei.value.code == -2
+
+
+@pytest.mark.parametrize("shape,window", [
+    ((2, 70, 16, 37), 3), ((1, 130, 16, 197), 5), ((3, 5, 16, 50), 7), ((2, 64, 16, 64), 12),
+    ((1, 64, 8, 100), 33), ((2, 20, 3, 29), 6), ((1, 7, 1, 63), 63), ((2, 64, 16, 200), 1000),
+    ((1, 66, 16, 131), 32), ((1, 64, 16, 64), 64),
+])
+@pytest.mark.parametrize("reverse", [False, True])
+def test_any_window_length(lb, oracle, shape, window, reverse):
+    """Window lengths without a fused kernel (the paper's figures use 3) run as two
+    passes: plain forward scan, then the local backward part."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    B, D, N, L = shape
+    s = make_inputs(B, D, N, L, seed=700 + L + window, random_A=True)
+    _run_fwd(lb, oracle, s, window=window, reverse=reverse)
+
+
+@pytest.mark.parametrize("nseg", [1, 3, 11])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_any_window_length_long_rows_in_segments(lb, oracle, nseg, dtype):
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(1, 70, 16, 1001, seed=720 + nseg, dtype=dtype)
+    lb.lbscan_set_option("segments", nseg)
+    try:
+        for window in (3, 24):
+            _run_fwd(lb, oracle, s, window=window, dtype=dtype)
+            _run_fwd(lb, oracle, s, window=window, dtype=dtype, reverse=True)
+    finally:
+        lb.lbscan_set_option("segments", 0)
+
+
+def test_any_window_length_default_segmentation_of_long_rows(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(1, 64, 16, 5000, seed=730)
+    _run_fwd(lb, oracle, s, window=6)
+
+
+def test_any_window_length_with_states(lb, oracle):
+    import torch
+    from gpu_util import assert_close, fwd_inputs, to_device, to_numpy
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(2, 64, 16, 90, seed=740)
+    h0 = np.random.default_rng(741).standard_normal((2, 64, 16)).astype(np.float32)
+    dev = to_device(s, "fp32")
+    out, hT = lb.lbscan_fwd(**fwd_inputs(dev), window=9, h0=torch.from_numpy(h0).cuda(), return_state=True)
+    torch.cuda.synchronize()
+    ref, ref_hT = oracle.fwd(**fwd_inputs(s), window=9, h0=h0, return_state=True)
+    assert_close(to_numpy(out), ref, "fp32", "out")
+    assert_close(to_numpy(hT), ref_hT, "fp32", "hT")
 
 
 def test_zero_timestep_is_skip_times_gate(lb):
