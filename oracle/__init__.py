@@ -4,8 +4,9 @@ TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
 benchmark's cpu_baseline leg.  Nothing in the product package imports this
 module, and this module imports nothing from the product package.
 
-The arithmetic lives in ``lbscan_oracle.c`` (plain sequential C, compiled with
-gcc); this file only builds it and marshals numpy fp64 arrays through ctypes.
+The arithmetic lives in ``lbscan_oracle.c`` (the scan) and ``conv1d_oracle.c``
+(the block's pre-scan convolution), plain sequential C compiled with gcc; this
+file only builds them and marshals numpy fp64 arrays through ctypes.
 """
 from __future__ import annotations
 
@@ -16,7 +17,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "lbscan_oracle.c")
+_SRCS = [os.path.join(_HERE, "lbscan_oracle.c"), os.path.join(_HERE, "conv1d_oracle.c")]
 _LIB = os.path.join(_HERE, "liblbscan_oracle.so")
 _lib = None
 
@@ -35,10 +36,10 @@ class _Problem(ctypes.Structure):
 
 def build(force: bool = False) -> str:
     """Compile the C oracle into a shared object next to its source."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or any(os.path.getmtime(_LIB) < os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
-               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+               "-ffp-contract=off", "-o", _LIB, *_SRCS, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -58,6 +59,11 @@ def _load():
         lib.lbscan_ref_fwd_state.argtypes = [ctypes.POINTER(_Problem), _dp, _dp, _dp]
         lib.lbscan_ref_bwd_state.restype = ctypes.c_int
         lib.lbscan_ref_bwd_state.argtypes = [ctypes.POINTER(_Problem)] + [_dp] * 12
+        ci = ctypes.c_int
+        lib.lbconv_ref_fwd.restype = ci
+        lib.lbconv_ref_fwd.argtypes = [ci] * 6 + [_dp] * 4
+        lib.lbconv_ref_bwd.restype = ci
+        lib.lbconv_ref_bwd.argtypes = [ci] * 6 + [_dp] * 7
         lib.lbscan_ref_num_threads.restype = ctypes.c_int
         lib.lbscan_ref_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -169,4 +175,35 @@ def bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout, windo
                                       _ptr(g["dDskip"]), _ptr(g["ddelta_bias"]), _ptr(g["dh0"]))
     if rc:
         raise RuntimeError(f"lbscan_ref_bwd_state failed: {rc}")
+    return g
+
+
+def conv1d_fwd(x, weight, bias=None, *, activation=True, reverse=False):
+    """Depthwise causal convolution along the last axis, then SiLU (pre-scan step
+    of the block).  x (B,D,L), weight (D,K), bias (D).  Returns y (B,D,L) fp64."""
+    x, weight, bias = _f64(x), _f64(weight), _f64(bias)
+    Bsz, D, L = x.shape
+    K = weight.shape[1]
+    assert weight.shape == (D, K) and (bias is None or bias.shape == (D,))
+    y = np.empty_like(x)
+    rc = _load().lbconv_ref_fwd(Bsz, D, L, K, int(bool(activation)), int(bool(reverse)),
+                                _ptr(x), _ptr(weight), _ptr(bias), _ptr(y))
+    if rc:
+        raise RuntimeError(f"lbconv_ref_fwd failed: {rc}")
+    return y
+
+
+def conv1d_bwd(x, weight, bias=None, *, dy, activation=True, reverse=False):
+    """Gradients of conv1d_fwd: dict with dx, dweight, dbias (None without bias)."""
+    x, weight, bias, dy = _f64(x), _f64(weight), _f64(bias), _f64(dy)
+    Bsz, D, L = x.shape
+    K = weight.shape[1]
+    assert dy.shape == x.shape
+    g = {"dx": np.empty_like(x), "dweight": np.empty((D, K)),
+         "dbias": np.empty((D,)) if bias is not None else None}
+    rc = _load().lbconv_ref_bwd(Bsz, D, L, K, int(bool(activation)), int(bool(reverse)),
+                                _ptr(x), _ptr(weight), _ptr(bias), _ptr(dy),
+                                _ptr(g["dx"]), _ptr(g["dweight"]), _ptr(g["dbias"]))
+    if rc:
+        raise RuntimeError(f"lbconv_ref_bwd failed: {rc}")
     return g
