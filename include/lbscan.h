@@ -136,6 +136,33 @@ int lbscan_bwd_state(const lbscan_args *fwd_args, const void *dout, const float 
  * alias fwd_set. */
 int lbscan_bidir_fwd(const lbscan_args *fwd_set, const lbscan_args *bwd_set, void *hip_stream);
 
+/* Pre-scan step of the block (Algorithm 1: x' = SiLU(Conv1d(x)), the line before
+ * B, C and Delta are projected from x').  The paper names the operation only; as
+ * in the Mamba block it extends, the convolution is depthwise and causal:
+ *     pre[b,d,t] = bias[d] + sum_{k<K} weight[d,k] x[b,d,t-(K-1)+k]   (x before 0 is 0)
+ *     y = pre * sigmoid(pre)          (y = pre when activation is 0)
+ * reverse = 1: the same operator on the time-reversed sequence (output t sees
+ * inputs t .. t+K-1), for blocks that scan right to left.  K = width in 1..4. */
+typedef struct lbscan_conv_args {
+    int32_t batch, dim, seqlen;   /* B, D, L; any may be 0 */
+    int32_t width;                /* K, 1..4 (else LBSCAN_EUNSUPPORTED) */
+    int32_t dtype;                /* storage type of x, y (and dy, dx); arithmetic is fp32 */
+    int32_t activation;           /* 1: SiLU, 0: none */
+    int32_t reverse;              /* 0/1 */
+    const void  *x;               /* (B,D,L) */
+    const float *weight;          /* (D,K) */
+    const float *bias;            /* (D) or NULL: 0 */
+    void        *y;               /* (B,D,L) out (not read by the backward call) */
+} lbscan_conv_args;
+
+int lbscan_conv1d_fwd(const lbscan_conv_args *args, void *hip_stream);
+
+/* Gradients of lbscan_conv1d_fwd: dx (B,D,L) in the storage type, dweight (D,K)
+ * and dbias (D; NULL iff bias is NULL) in fp32, all overwritten; the two sums
+ * over batch and time are accumulated with fp32 atomics.  No workspace. */
+int lbscan_conv1d_bwd(const lbscan_conv_args *fwd_args, const void *dy,
+                      void *dx, float *dweight, float *dbias, void *hip_stream);
+
 /* Bytes of device scratch the call named by `which` (LBSCAN_WS_*) needs for
  * these sizes; 0 means workspace may be NULL. */
 size_t lbscan_workspace_bytes(const lbscan_args *args, int which);

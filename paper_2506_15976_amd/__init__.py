@@ -5,6 +5,7 @@ The computation lives in hand-written HIP kernels behind a C ABI
 binding with the same entry-point names.
 """
 from .binding import (  # noqa: F401
-    LbscanArgs, LbscanError, lbscan_bidir_fwd, lbscan_bwd, lbscan_default_window, lbscan_fwd, lbscan_saved_state,
-    lbscan_set_option, lbscan_version, lbscan_workspace_bytes, load, make_args,
+    LbscanArgs, LbscanConvArgs, LbscanError, lbscan_bidir_fwd, lbscan_bwd, lbscan_conv1d_bwd, lbscan_conv1d_fwd,
+    lbscan_default_window, lbscan_fwd, lbscan_saved_state, lbscan_set_option, lbscan_version,
+    lbscan_workspace_bytes, load, make_args,
 )

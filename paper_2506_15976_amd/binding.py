@@ -20,7 +20,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 EXPORTS = (
     "lbscan_fwd", "lbscan_bwd", "lbscan_bidir_fwd", "lbscan_workspace_bytes",
     "lbscan_default_window", "lbscan_strerror", "lbscan_last_error", "lbscan_version",
-    "lbscan_set_option", "lbscan_bwd_state",
+    "lbscan_set_option", "lbscan_bwd_state", "lbscan_conv1d_fwd", "lbscan_conv1d_bwd",
 )
 
 
@@ -36,6 +36,17 @@ class LbscanArgs(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("saved_state", ctypes.c_void_p), ("saved_state_bytes", ctypes.c_size_t),
         ("h0", ctypes.c_void_p), ("hT", ctypes.c_void_p),
+    ]
+
+
+class LbscanConvArgs(ctypes.Structure):
+    """Mirror of struct lbscan_conv_args."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("dim", ctypes.c_int32), ("seqlen", ctypes.c_int32),
+        ("width", ctypes.c_int32), ("dtype", ctypes.c_int32), ("activation", ctypes.c_int32),
+        ("reverse", ctypes.c_int32),
+        ("x", ctypes.c_void_p), ("weight", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+        ("y", ctypes.c_void_p),
     ]
 
 
@@ -70,6 +81,11 @@ def load():
     lib.lbscan_bwd.argtypes = [ap] + [vp] * 10
     lib.lbscan_bwd_state.restype = ctypes.c_int
     lib.lbscan_bwd_state.argtypes = [ap] + [vp] * 12
+    cp = ctypes.POINTER(LbscanConvArgs)
+    lib.lbscan_conv1d_fwd.restype = ctypes.c_int
+    lib.lbscan_conv1d_fwd.argtypes = [cp, vp]
+    lib.lbscan_conv1d_bwd.restype = ctypes.c_int
+    lib.lbscan_conv1d_bwd.argtypes = [cp] + [vp] * 5
     lib.lbscan_workspace_bytes.restype = ctypes.c_size_t
     lib.lbscan_workspace_bytes.argtypes = [ap, ctypes.c_int]
     lib.lbscan_default_window.restype = ctypes.c_int
@@ -262,4 +278,43 @@ def lbscan_bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout
                                      _ptr(g["dh0"]), _stream(stream))
         _check(rc, "lbscan_bwd_state")
     del ws
+    return g
+
+
+def _conv_args(x, weight, bias, activation, reverse, y=None):
+    import torch
+    Bsz, D, L = x.shape
+    K = weight.shape[1]
+    if tuple(weight.shape) != (D, K) or weight.dtype != torch.float32:
+        raise LbscanError(EINVAL, f"weight: expected ({D}, K) float32")
+    if bias is not None and (tuple(bias.shape) != (D,) or bias.dtype != torch.float32):
+        raise LbscanError(EINVAL, f"bias: expected ({D},) float32")
+    for name, t in (("x", x), ("weight", weight), ("bias", bias), ("y", y)):
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise LbscanError(EINVAL, f"{name} must be a contiguous device tensor")
+    return LbscanConvArgs(Bsz, D, L, K, _dtype_code(x), int(bool(activation)), int(bool(reverse)),
+                          _ptr(x), _ptr(weight), _ptr(bias), _ptr(y))
+
+
+def lbscan_conv1d_fwd(x, weight, bias=None, *, activation=True, reverse=False, out=None, stream=None):
+    """y = SiLU(depthwise causal conv of x along the last axis) (see include/lbscan.h).
+    x (B,D,L), weight (D,K) fp32 with K <= 4, bias (D) fp32."""
+    import torch
+    y = torch.empty_like(x) if out is None else out
+    a = _conv_args(x, weight, bias, activation, reverse, y)
+    _check(load().lbscan_conv1d_fwd(ctypes.byref(a), _stream(stream)), "lbscan_conv1d_fwd")
+    return y
+
+
+def lbscan_conv1d_bwd(x, weight, bias=None, *, dy, activation=True, reverse=False, stream=None):
+    """Gradients of lbscan_conv1d_fwd: dict with dx, dweight, dbias (None without bias)."""
+    import torch
+    if tuple(dy.shape) != tuple(x.shape) or dy.dtype != x.dtype or not dy.is_contiguous():
+        raise LbscanError(EINVAL, "dy must match x")
+    a = _conv_args(x, weight, bias, activation, reverse)
+    g = dict(dx=torch.empty_like(x), dweight=torch.empty_like(weight),
+             dbias=torch.empty_like(bias) if bias is not None else None)
+    rc = load().lbscan_conv1d_bwd(ctypes.byref(a), _ptr(dy), _ptr(g["dx"]), _ptr(g["dweight"]),
+                                  _ptr(g["dbias"]), _stream(stream))
+    _check(rc, "lbscan_conv1d_bwd")
     return g

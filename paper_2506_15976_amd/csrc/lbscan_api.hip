@@ -86,6 +86,31 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     return p;
 }
 
+int check_conv_args(const lbscan_conv_args* a, bool* empty)
+{
+    *empty = false;
+    if (!a) return LBSCAN_EINVAL;
+    if (a->batch < 0 || a->dim < 0 || a->seqlen < 0 || a->width < 1) return LBSCAN_EINVAL;
+    if (a->dtype != LBSCAN_FP32 && a->dtype != LBSCAN_BF16) return LBSCAN_EUNSUPPORTED;
+    if (a->width > 4) return LBSCAN_EUNSUPPORTED;
+    if ((a->reverse != 0 && a->reverse != 1) || (a->activation != 0 && a->activation != 1)) return LBSCAN_EINVAL;
+    if (a->seqlen > (1 << 28)) return LBSCAN_EUNSUPPORTED;     // token offsets are 32-bit
+    if ((long)a->batch * a->dim * a->seqlen == 0) { *empty = true; return LBSCAN_OK; }
+    if (!a->x || !a->weight) return LBSCAN_EINVAL;
+    if (!aligned4(a->x) || !aligned4(a->weight) || (a->bias && !aligned4(a->bias))) return LBSCAN_EINVAL;
+    return LBSCAN_OK;
+}
+
+lbscan::ConvParams to_conv_params(const lbscan_conv_args* a)
+{
+    lbscan::ConvParams p;
+    p.batch = a->batch; p.dim = a->dim; p.seqlen = a->seqlen; p.width = a->width;
+    p.dtype = a->dtype; p.activation = a->activation; p.reverse = a->reverse;
+    p.x = a->x; p.weight = a->weight; p.bias = a->bias; p.y = a->y;
+    p.dy = nullptr; p.dx = nullptr; p.dweight = nullptr; p.dbias = nullptr;
+    return p;
+}
+
 }  // namespace
 
 extern "C" {
@@ -226,6 +251,31 @@ int lbscan_bwd_state(const lbscan_args* a, const void* dout, const float* dhT,
     }
     hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, saved, dhT, s);
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bwd");
+}
+
+int lbscan_conv1d_fwd(const lbscan_conv_args* a, void* hip_stream)
+{
+    bool empty;
+    int rc = check_conv_args(a, &empty);
+    if (rc != LBSCAN_OK || empty) return rc;
+    if (!a->y || !aligned4(a->y)) return LBSCAN_EINVAL;
+    hipError_t e = lbscan::launch_conv1d_fwd(to_conv_params(a), static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_conv1d_fwd");
+}
+
+int lbscan_conv1d_bwd(const lbscan_conv_args* a, const void* dy, void* dx, float* dweight, float* dbias,
+                      void* hip_stream)
+{
+    bool empty;
+    int rc = check_conv_args(a, &empty);
+    if (rc != LBSCAN_OK) return rc;
+    if ((long)a->dim * a->width > 0 && (!dweight || !aligned4(dweight))) return LBSCAN_EINVAL;
+    if (a->bias && (!dbias || !aligned4(dbias))) return LBSCAN_EINVAL;
+    if (!empty && (!dy || !dx || !aligned4(dy) || !aligned4(dx))) return LBSCAN_EINVAL;
+    lbscan::ConvParams p = to_conv_params(a);
+    p.y = nullptr; p.dy = dy; p.dx = dx; p.dweight = dweight; p.dbias = a->bias ? dbias : nullptr;
+    hipError_t e = lbscan::launch_conv1d_bwd(p, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_conv1d_bwd");
 }
 
 size_t lbscan_workspace_bytes(const lbscan_args* a, int which)

@@ -87,6 +87,20 @@ struct BwdParams {
     float* dh0;           // (B*D, N), nullable: psi leaving the row on the left
 };
 
+// Arguments of the pre-scan convolution kernels (lbscan_conv.hip).
+struct ConvParams {
+    int batch, dim, seqlen, width;
+    int dtype, activation, reverse;
+    const void* x;
+    const float* weight;
+    const float* bias;    // nullable
+    void* y;              // forward only
+    const void* dy;       // backward only
+    void* dx;
+    float* dweight;       // (D,K), zeroed by the launcher
+    float* dbias;         // (D), nullable
+};
+
 constexpr int kTileTokens = 16;      // tokens per tile of the backward kernel = checkpoint spacing
 constexpr int kFwdTileTokens = 32;   // tokens per tile of the forward kernel (128 bytes of an fp32 row)
 
@@ -130,6 +144,10 @@ hipError_t launch_zero(float* dst, long n, hipStream_t stream);
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
                       const float* saved, const float* dhT, hipStream_t stream);
 size_t bwd_workspace_bytes(const FwdParams& f);
+
+// Depthwise causal convolution + SiLU along the sequence and its gradient.
+hipError_t launch_conv1d_fwd(const ConvParams& p, hipStream_t stream);
+hipError_t launch_conv1d_bwd(const ConvParams& p, hipStream_t stream);
 
 // Chains the per-segment summaries into the states entering each segment
 // (lbscan_carry.hip): carry[s] <- exclusive scan over s of (exp(A*dsum), carry),

@@ -21,7 +21,7 @@ def lib():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "lbscan.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lbscan_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(lbscan_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -37,6 +37,10 @@ def test_struct_layout_matches_header():
     # 8 int32 + 9 pointers + (workspace pointer, size_t) + (saved_state pointer, size_t)
     assert ctypes.sizeof(LbscanArgs) == 8 * 4 + 10 * 8 + 8 + 16 + 16
     assert LbscanArgs.x.offset == 32
+    from paper_2506_15976_amd.binding import LbscanConvArgs
+    # 7 int32 (padded to 32 bytes) + 4 pointers
+    assert ctypes.sizeof(LbscanConvArgs) == 32 + 4 * 8
+    assert LbscanConvArgs.x.offset == 32
     assert LbscanArgs.workspace_bytes.offset == 32 + 10 * 8
     assert LbscanArgs.saved_state.offset == 32 + 11 * 8
 
