@@ -108,6 +108,7 @@ lbscan::ConvParams to_conv_params(const lbscan_conv_args* a)
     p.dtype = a->dtype; p.activation = a->activation; p.reverse = a->reverse;
     p.x = a->x; p.weight = a->weight; p.bias = a->bias; p.y = a->y;
     p.dy = nullptr; p.dx = nullptr; p.dweight = nullptr; p.dbias = nullptr;
+    p.items_per_wave = 1;
     return p;
 }
 

@@ -99,6 +99,7 @@ struct ConvParams {
     void* dx;
     float* dweight;       // (D,K), zeroed by the launcher
     float* dbias;         // (D), nullable
+    int items_per_wave;   // set by the launcher
 };
 
 constexpr int kTileTokens = 16;      // tokens per tile of the backward kernel = checkpoint spacing
