@@ -28,7 +28,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # at half rate on this chip (measured), i.e. it takes two issue slots.
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
 # Issue slots per state update of rowlane_fwd_kernel, from SQ_INSTS_VALU and
-# SQ_INSTS_VALU_TRANS_F32 of profiles/ (10.7 VALU instructions incl. 1.3 transcendental).
+# SQ_INSTS_VALU_TRANS_F32 in profiles/lbscan_counters_vim_small.md (10.7 VALU instructions
+# incl. 1.3 transcendental).
 FWD_SLOTS_PER_STATE_UPDATE = 12.0
 FWD_KEYS = ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")
 
@@ -232,6 +233,15 @@ def main():
         assert train_call(*g_args[0]) == 0, "training step failed"
         ms_train = time_calls([(lambda g=g: train_call(*g)) for g in g_args], max(a.steps // 4, 1), max(a.warmup // 4, 1))
 
+    # the block's pre-scan step (depthwise causal conv + SiLU, width 4) on the same x
+    # tensors: an HBM-bound kernel of the same library, timed as extra information
+    wconv = torch.randn(w["dim"], 4, device="cuda:0") * 0.5
+    bconv = torch.randn(w["dim"], device="cuda:0")
+    conv_sets = list(zip(sets, ys))[:max(2, min(nsets, 4))]
+    conv_calls = [(lambda s_=s_, y_=y_: lb.lbscan_conv1d_fwd(s_["x"], wconv, bconv, out=y_)) for s_, y_ in conv_sets]
+    ms_conv = time_calls(conv_calls, max(a.steps // 4, 1), max(a.warmup // 4, 1))
+    conv_bytes = 2 * w["batch"] * w["dim"] * w["seqlen"] * (2 if w["dtype"] == "bf16" else 4)
+
     tokens = w["batch"] * w["seqlen"]
     # average launch duration over the timed region (includes the ~5 us gap between
     # dependent launches; an event pair per launch reads slightly more, a kernel trace less)
@@ -285,6 +295,8 @@ def main():
         "bwd_ms": ms_bwd,
         "fwd_plus_bwd_ms": ms_train,
         "bwd_algorithmic_gbps": None if ms_bwd is None else algorithmic_bytes(w, "bwd") / (ms_bwd * 1e-3) / 1e9,
+        "prescan_conv_fwd_ms": ms_conv,
+        "prescan_conv_fwd_gbps": conv_bytes / (ms_conv * 1e-3) / 1e9,
     }
     print(json.dumps(line))
 
