@@ -60,6 +60,23 @@ __global__ void __launch_bounds__(256) zero_kernel(float* __restrict__ dst, long
     if (i < n) dst[i] = 0.0f;
 }
 
+// Clears up to kZeroMany buffers in one launch: block x belongs to the buffer whose
+// range of blocks contains it.
+__global__ void __launch_bounds__(256) zero_many_kernel(const ZeroMany z)
+{
+    long blk = blockIdx.x;
+#pragma unroll
+    for (int k = 0; k < kZeroMany; ++k) {
+        const long nb = (z.n[k] + 255) / 256;
+        if (blk < nb) {
+            const long i = blk * 256 + threadIdx.x;
+            if (i < z.n[k]) z.dst[k][i] = 0.0f;
+            return;
+        }
+        blk -= nb;
+    }
+}
+
 __global__ void __launch_bounds__(256)
 copy_kernel(float* __restrict__ dst, const float* __restrict__ src, long n)
 {
@@ -82,6 +99,19 @@ hipError_t launch_zero(float* dst, long n, hipStream_t stream)
 {
     if (n <= 0 || !dst) return hipSuccess;
     hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, dst, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_many(ZeroMany z, hipStream_t stream)
+{
+    long blocks = 0;
+    for (int k = 0; k < kZeroMany; ++k) {
+        if (!z.dst[k] || z.n[k] < 0) z.n[k] = 0;
+        blocks += (z.n[k] + 255) / 256;
+    }
+    if (blocks == 0) return hipSuccess;
+    if (blocks > 0x7fffffffL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(zero_many_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, z);
     return hipGetLastError();
 }
 

@@ -206,11 +206,9 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
     p.psi_in = s.nseg > 1 ? ws + l.psi : dhT;
 
     hipError_t e;
-    if ((e = launch_zero(p.dBacc, bnl, stream)) != hipSuccess) return e;
-    if ((e = launch_zero(p.dCacc, bnl, stream)) != hipSuccess) return e;
-    if ((e = launch_zero(p.dA, (long)f.dim * f.dstate, stream)) != hipSuccess) return e;
-    if ((e = launch_zero(p.dDskip, f.dim, stream)) != hipSuccess) return e;
-    if ((e = launch_zero(p.dbias, f.dim, stream)) != hipSuccess) return e;
+    const ZeroMany z{{p.dBacc, p.dCacc, p.dA, p.dDskip, p.dbias},
+                     {bnl, bnl, (long)f.dim * f.dstate, f.dim, f.dim}};
+    if ((e = launch_zero_many(z, stream)) != hipSuccess) return e;
 
     if (saved && s.nseg == 1) {
         // the forward call left the checkpoints (entering state included): no summary pass

@@ -136,6 +136,10 @@ hipError_t launch_convert_bf16(const float* src, void* dst, long n, hipStream_t 
 // Sets n floats to zero with a kernel (a memset node must not be recorded into
 // a captured graph).
 hipError_t launch_zero(float* dst, long n, hipStream_t stream);
+// The same for several buffers in one launch (null or empty entries are skipped).
+constexpr int kZeroMany = 5;
+struct ZeroMany { float* dst[kZeroMany]; long n[kZeroMany]; };
+hipError_t launch_zero_many(ZeroMany z, hipStream_t stream);
 
 // Whole backward pass: zero the accumulators, checkpoint pass, backward kernel,
 // conversion of dBm / dCm when the storage type is not fp32.  dBm / dCm are the
