@@ -161,3 +161,19 @@ def test_missing_workspace_is_an_error(lb):
                               o["dz"].data_ptr(), o["dB"].data_ptr(), o["dC"].data_ptr(), o["dA"].data_ptr(),
                               o["dD"].data_ptr(), o["db"].data_ptr(), None)
     assert rc == -3
+
+
+def test_gradients_with_extreme_time_steps_and_decay_rates(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(2, 64, 16, 150, seed=9200, with_dout=True)
+    r = np.random.default_rng(9201)
+    s["delta"] = r.choice(np.array([-90.0, -12.0, -1.0, 0.5, 3.0, 25.0], dtype=np.float32),
+                          size=s["delta"].shape).astype(np.float32)
+    s["delta_bias"] = np.zeros_like(s["delta_bias"])
+    s["A"] = -r.choice(np.array([1e-3, 0.5, 4.0, 40.0, 1e3], dtype=np.float32), size=s["A"].shape).astype(np.float32)
+    for nseg in (0, 3):
+        lb.lbscan_set_option("segments", nseg)
+        try:
+            _run_bwd(lb, oracle, s, window=4)
+        finally:
+            lb.lbscan_set_option("segments", 0)

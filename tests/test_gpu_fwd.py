@@ -248,3 +248,24 @@ def test_bidir_small_and_ragged(lb, oracle):
 def test_bidir_vim_tiny(lb, oracle):
     from paper_2506_15976_amd.inputs import make_workload
     _run_bidir(lb, oracle, make_workload("vim_tiny"), make_workload("vim_tiny", direction_b=True))
+
+
+def test_extreme_time_steps_and_decay_rates(lb, oracle):
+    """Time steps from the linear branch of softplus (argument above 20) down to
+    underflow, decay rates up to abar = 0, and rows cut into segments: nothing
+    overflows and the result stays within the parity bar."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(2, 64, 16, 300, seed=9100, with_dout=True)
+    r = np.random.default_rng(9101)
+    s["delta"] = r.choice(np.array([-90.0, -12.0, -1.0, 0.5, 3.0, 25.0], dtype=np.float32),
+                          size=s["delta"].shape).astype(np.float32)
+    s["delta_bias"] = np.zeros_like(s["delta_bias"])
+    s["A"] = -r.choice(np.array([1e-3, 0.5, 4.0, 40.0, 1e3], dtype=np.float32), size=s["A"].shape).astype(np.float32)
+    for nseg in (0, 3):
+        lb.lbscan_set_option("segments", nseg)
+        try:
+            _run_fwd(lb, oracle, s, window=4)
+            _run_fwd(lb, oracle, s, window=4, reverse=True)
+            _run_fwd(lb, oracle, s, window=7)
+        finally:
+            lb.lbscan_set_option("segments", 0)
