@@ -88,3 +88,14 @@ def test_workspace_sizes(lib):
     assert lib.lbscan_workspace_bytes(ctypes.byref(a), WS_BIDIR) == 0
     a.dtype = 1
     assert lib.lbscan_workspace_bytes(ctypes.byref(a), WS_BIDIR) == 2 * 8 * 10 * 4
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/lbscan.h compiles as C99 on its own (no C++ or framework types)."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "lbscan.h"\n'
+                   'int main(void) { lbscan_args a; lbscan_conv_args c; (void)a; (void)c;\n'
+                   '  return sizeof(a) == 0 || sizeof(c) == 0; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)
