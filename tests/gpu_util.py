@@ -3,8 +3,7 @@ same (storage-rounded) values, compare with the scale-aware error metric."""
 import numpy as np
 import torch
 
-from paper_2506_15976_amd.inputs import (bf16_bits_to_fp32, error_metric, fp32_to_bf16_bits,
-                                         make_inputs, make_workload, mean_error)
+from paper_2506_15976_amd.inputs import bf16_bits_to_fp32, error_metric, fp32_to_bf16_bits, mean_error
 
 TENSOR_KEYS = ("x", "delta", "Bm", "Cm", "z", "dout")
 PARAM_KEYS = ("A", "Dskip", "delta_bias")

@@ -3,7 +3,6 @@ memset node), so a call can be recorded into a HIP graph.  Every replay is check
 against the eager result, with eager work and synchronisations between replays."""
 import ctypes
 
-import numpy as np
 import pytest
 
 pytestmark = pytest.mark.gpu
