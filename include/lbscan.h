@@ -59,9 +59,9 @@ typedef struct lbscan_args {
     int32_t batch, dim, dstate, seqlen;  /* B, D, N, L; any may be 0 (then nothing is done)   */
     int32_t window;           /* M >= 1.  M in {1,2,4,8,16} (and any M >= L when L <= 16) runs
                                  the fused single-pass kernels, forward and backward.  Any other
-                                 M runs lbscan_fwd as two passes over HBM (plain forward scan,
-                                 then the local backward part); lbscan_bwd then returns
-                                 LBSCAN_EUNSUPPORTED */
+                                 M runs as two passes over HBM each way (the plain scan with
+                                 window 1, then the local backward part): lbscan_fwd for every
+                                 M, lbscan_bwd for M <= 16 (LBSCAN_EUNSUPPORTED beyond) */
     int32_t dtype;            /* LBSCAN_FP32 or LBSCAN_BF16: storage type of the (B,D,L) and
                                  (B,N,L) tensors; arithmetic is fp32 either way                */
     int32_t delta_softplus;   /* 0/1: apply softplus to delta + delta_bias (Algorithm 1)      */

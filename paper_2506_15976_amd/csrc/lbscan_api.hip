@@ -227,10 +227,17 @@ int lbscan_bwd_state(const lbscan_args* a, const void* dout, const float* dhT,
     const void* ptrs[] = {dout, dx, ddelta, dz, dBm, dCm, dA, dDskip, ddelta_bias, dhT, dh0};
     for (const void* q : ptrs)
         if (q && !aligned4(q)) return LBSCAN_EINVAL;
-    const int M = effective_window(a->window, a->seqlen);
-    if (M == 0) return LBSCAN_EUNSUPPORTED;
+    int M = effective_window(a->window, a->seqlen);
+    int local_window = 0;
+    if (M == 0) {
+        // no fused kernel for this window length: the fused kernel with window 1, then
+        // the local backward part by a kernel of its own (windows up to one tile)
+        local_window = a->window < a->seqlen ? a->window : a->seqlen;
+        if (local_window > lbscan::kTileTokens) return LBSCAN_EUNSUPPORTED;
+        M = 1;
+    }
     lbscan::FwdParams f = to_params(a, M);
-    const size_t need = lbscan::bwd_workspace_bytes(f);
+    const size_t need = lbscan::bwd_workspace_bytes(f, local_window);
     if (need && (!a->workspace || a->workspace_bytes < need || !aligned4(a->workspace)))
         return LBSCAN_EWORKSPACE;
     lbscan::BwdParams p;
@@ -243,14 +250,15 @@ int lbscan_bwd_state(const lbscan_args* a, const void* dout, const float* dhT,
     p.dA = dA; p.dDskip = a->Dskip ? dDskip : nullptr; p.dbias = a->delta_bias ? ddelta_bias : nullptr;
     p.ckpt = nullptr; p.nseg = 1; p.seg_tiles = 0; p.cum = nullptr; p.carry = nullptr; p.psi_in = nullptr;
     p.dh0 = dh0;
+    p.part_dx = nullptr; p.part_ddelta = nullptr; p.part_dz = nullptr;
     f.hT = nullptr;
     const float* saved = nullptr;
-    if (a->saved_state) {
+    if (a->saved_state && local_window == 0) {
         const size_t sneed = lbscan::saved_state_bytes(f);
         if (sneed && (a->saved_state_bytes < sneed || !aligned4(a->saved_state))) return LBSCAN_EWORKSPACE;
         if (sneed) saved = static_cast<const float*>(a->saved_state);
     }
-    hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, saved, dhT, s);
+    hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, saved, dhT, local_window, s);
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bwd");
 }
 
@@ -286,10 +294,14 @@ size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
     const size_t bdl = (size_t)a->batch * a->dim * a->seqlen;
     int M = effective_window(a->window, a->seqlen);
     if (M == 0) {
-        // forward only, as two launches; there is no backward pass for this window length
+        // two launches each way: the plain scan with window 1 and the local backward part
         if (which == LBSCAN_WS_FWD)
             return lbscan::fwd_generic_workspace_bytes(to_params(a, a->window < a->seqlen ? a->window : a->seqlen));
-        if (which != LBSCAN_WS_BIDIR) return 0;
+        if (which == LBSCAN_WS_SAVED) return 0;
+        if (which == LBSCAN_WS_BWD) {
+            const int lw = a->window < a->seqlen ? a->window : a->seqlen;
+            return lw > lbscan::kTileTokens ? 0 : lbscan::bwd_workspace_bytes(to_params(a, 1), lw);
+        }
         M = 1;
     }
     switch (which) {

@@ -154,11 +154,11 @@ namespace {
 struct BwdLayout {
     Shape shape;            // segments in forward tiles (32 tokens)
     size_t ntiles16;        // backward tiles (16 tokens) per row
-    size_t ckpt, cum, carry, dsum, psi, acc;   // float offsets into the workspace
+    size_t ckpt, cum, carry, dsum, psi, acc, part;   // float offsets into the workspace
     size_t total;           // floats
 };
 
-BwdLayout bwd_layout(const FwdParams& f)
+BwdLayout bwd_layout(const FwdParams& f, int local_window)
 {
     BwdLayout l;
     l.shape = pick_shape(f);
@@ -173,27 +173,35 @@ BwdLayout bwd_layout(const FwdParams& f)
     l.psi = o;   o += ns * rows * N;
     l.acc = o;
     if (f.dtype != 0) o += 2 * (size_t)f.batch * N * f.seqlen;     // fp32 dBm, dCm
+    l.part = o;
+    // fp32 dx, ddelta, dz of the fused kernel, for the kernel of the local backward part
+    if (f.dtype != 0 && local_window > 0) o += 3 * rows * (size_t)f.seqlen;
     l.total = o;
     return l;
 }
 
 }  // namespace
 
-size_t bwd_workspace_bytes(const FwdParams& f)
+size_t bwd_workspace_bytes(const FwdParams& f, int local_window)
 {
     if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return 0;
-    return bwd_layout(f).total * sizeof(float);
+    return bwd_layout(f, local_window).total * sizeof(float);
 }
 
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
-                      const float* saved, const float* dhT, hipStream_t stream)
+                      const float* saved, const float* dhT, int local_window, hipStream_t stream)
 {
     if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return hipSuccess;
     if (!workspace) return hipErrorInvalidValue;
-    const BwdLayout l = bwd_layout(f);
+    const BwdLayout l = bwd_layout(f, local_window);
     const Shape& s = l.shape;
     float* ws = static_cast<float*>(workspace);
     const long bnl = (long)f.batch * f.dstate * f.seqlen;
+    const size_t bdl = (size_t)f.batch * f.dim * f.seqlen;
+    const bool parts = f.dtype != 0 && local_window > 0;
+    p.part_dx = parts ? ws + l.part : nullptr;
+    p.part_ddelta = parts ? ws + l.part + bdl : nullptr;
+    p.part_dz = parts ? ws + l.part + 2 * bdl : nullptr;
     p.dBacc = f.dtype == 0 ? static_cast<float*>(dBm) : ws + l.acc;
     p.dCacc = f.dtype == 0 ? static_cast<float*>(dCm) : ws + l.acc + bnl;
     p.ckpt = ws + l.ckpt;
@@ -210,18 +218,40 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
                      {bnl, bnl, (long)f.dim * f.dstate, f.dim, f.dim}};
     if ((e = launch_zero_many(z, stream)) != hipSuccess) return e;
 
+    // what follows the fused kernel: the local backward part of a window length
+    // without a fused kernel (independent tiles of whole windows, cut into enough
+    // segments to fill the chip), then the conversion of the fp32 accumulators
+    auto finish = [&]() -> hipError_t {
+        hipError_t r = hipSuccess;
+        if (local_window > 0) {
+            BwdParams q = p;
+            q.window = local_window;
+            const long tl = (long)(kTileTokens / local_window) * local_window;
+            const long ntiles = (f.seqlen + tl - 1) / tl;
+            const long nrb = (long)((f.dim + 63) / 64) * f.batch;
+            long want = nrb < 512 ? (512 + nrb - 1) / nrb : 1;       // two blocks per CU are resident
+            if (f.force_nseg >= 1) want = f.force_nseg;
+            long st = (ntiles + want - 1) / want;
+            if (st < 1) st = 1;
+            q.seg_tiles = (int)st;
+            q.nseg = (int)((ntiles + st - 1) / st);
+            r = f.dtype == 0 ? launch_bwd_local_f32(q, stream) : launch_bwd_local_bf16(q, stream);
+            if (r != hipSuccess) return r;
+        }
+        if (f.dtype != 0) {
+            if ((r = launch_convert_bf16(p.dBacc, dBm, bnl, stream)) != hipSuccess) return r;
+            if ((r = launch_convert_bf16(p.dCacc, dCm, bnl, stream)) != hipSuccess) return r;
+        }
+        return r;
+    };
+
     if (saved && s.nseg == 1) {
         // the forward call left the checkpoints (entering state included): no summary pass
         p.ckpt = saved;
         p.cum = nullptr;
         p.carry = nullptr;
         e = f.dtype == 0 ? launch_bwd_rowlane_f32(p, stream) : launch_bwd_rowlane_bf16(p, stream);
-        if (e != hipSuccess) return e;
-        if (f.dtype != 0) {
-            if ((e = launch_convert_bf16(p.dBacc, dBm, bnl, stream)) != hipSuccess) return e;
-            if ((e = launch_convert_bf16(p.dCacc, dCm, bnl, stream)) != hipSuccess) return e;
-        }
-        return hipSuccess;
+        return e != hipSuccess ? e : finish();
     }
 
     // summary pass (the forward kernel in summary mode): checkpoints of f for every
@@ -246,12 +276,7 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
     }
 
     e = f.dtype == 0 ? launch_bwd_rowlane_f32(p, stream) : launch_bwd_rowlane_bf16(p, stream);
-    if (e != hipSuccess) return e;
-    if (f.dtype != 0) {
-        if ((e = launch_convert_bf16(p.dBacc, dBm, bnl, stream)) != hipSuccess) return e;
-        if ((e = launch_convert_bf16(p.dCacc, dCm, bnl, stream)) != hipSuccess) return e;
-    }
-    return hipSuccess;
+    return e != hipSuccess ? e : finish();
 }
 
 }  // namespace lbscan

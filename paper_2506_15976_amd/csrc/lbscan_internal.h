@@ -85,6 +85,13 @@ struct BwdParams {
     const float* carry;   // (nseg, B*D, N): forward state entering each segment (null: zeros)
     const float* psi_in;  // (nseg, B*D, N): psi entering each segment from the right
     float* dh0;           // (B*D, N), nullable: psi leaving the row on the left
+    // (B,D,L) fp32, nullable.  When set, the fused kernel leaves dx, ddelta, dz here
+    // instead of in dx, ddelta, dz, and the kernel of the local backward part
+    // reads them from here, adds its share and writes dx, ddelta, dz: with 2-byte
+    // storage the two shares must meet in fp32 (they may cancel).
+    float* part_dx;
+    float* part_ddelta;
+    float* part_dz;
 };
 
 // Arguments of the pre-scan convolution kernels (lbscan_conv.hip).
@@ -131,6 +138,11 @@ size_t saved_state_bytes(const FwdParams& p);
 // Backward kernels (lbscan_bwd_rowlane.inc), one translation unit per storage type.
 hipError_t launch_bwd_rowlane_f32(const BwdParams& p, hipStream_t stream);
 hipError_t launch_bwd_rowlane_bf16(const BwdParams& p, hipStream_t stream);
+// Backward kernel of the local backward part alone (lbscan_bwd_local.inc): adds its
+// gradients to what the fused kernel left for window 1.  p.window <= kTileTokens;
+// p.seg_tiles counts tiles of (kTileTokens / window) * window tokens.
+hipError_t launch_bwd_local_f32(const BwdParams& p, hipStream_t stream);
+hipError_t launch_bwd_local_bf16(const BwdParams& p, hipStream_t stream);
 hipError_t launch_convert_f32(const float* src, void* dst, long n, hipStream_t stream);
 hipError_t launch_convert_bf16(const float* src, void* dst, long n, hipStream_t stream);
 // Sets n floats to zero with a kernel (a memset node must not be recorded into
@@ -146,9 +158,11 @@ hipError_t launch_zero_many(ZeroMany z, hipStream_t stream);
 // caller's outputs; workspace must hold bwd_workspace_bytes(f) bytes.
 // saved (nullable): checkpoints left by launch_fwd on the same inputs.
 // dhT (nullable): gradient arriving at the state that leaves the row.
+// local_window > 0: f.window is 1 and the gradients of the local backward part for
+// that window length (<= kTileTokens, no fused kernel) are added by a second kernel.
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
-                      const float* saved, const float* dhT, hipStream_t stream);
-size_t bwd_workspace_bytes(const FwdParams& f);
+                      const float* saved, const float* dhT, int local_window, hipStream_t stream);
+size_t bwd_workspace_bytes(const FwdParams& f, int local_window = 0);
 
 // Depthwise causal convolution + SiLU along the sequence and its gradient.
 hipError_t launch_conv1d_fwd(const ConvParams& p, hipStream_t stream);

@@ -70,8 +70,9 @@ def test_validation_without_gpu(lib):
     a.seqlen = 64
     a.window = 3
     a.x = a.delta = a.y = a.A = a.Bm = a.Cm = 256                   # never dereferenced on the host
-    # a window length without a fused kernel has a forward path (two passes) but no backward pass
+    # the backward pass of window lengths without a fused kernel stops at 16 tokens
     fake = ctypes.c_void_p(256)
+    a.window = 17
     assert lib.lbscan_bwd(ctypes.byref(a), *([fake] * 9), None) == EUNSUPPORTED
     a.x = 257
     a.window = 4

@@ -177,3 +177,40 @@ def test_gradients_with_extreme_time_steps_and_decay_rates(lb, oracle):
             _run_bwd(lb, oracle, s, window=4)
         finally:
             lb.lbscan_set_option("segments", 0)
+
+
+
+@pytest.mark.parametrize("shape,window", [
+    ((2, 70, 16, 37), 3), ((1, 130, 16, 197), 5), ((3, 5, 16, 50), 7), ((2, 64, 16, 64), 12),
+    ((1, 64, 8, 100), 6), ((2, 20, 3, 29), 9), ((1, 7, 1, 63), 15), ((2, 64, 16, 10), 11),
+    ((1, 66, 16, 131), 13), ((1, 64, 16, 48), 14),
+])
+@pytest.mark.parametrize("reverse", [False, True])
+def test_gradients_any_window_up_to_a_tile(lb, oracle, shape, window, reverse):
+    """Window lengths without a fused kernel: gradients of the plain scan from the
+    fused kernel with window 1 plus those of the local backward part."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    B, D, N, L = shape
+    s = make_inputs(B, D, N, L, seed=9400 + L + window, with_dout=True, random_A=True)
+    _run_bwd(lb, oracle, s, window=window, reverse=reverse)
+
+
+@pytest.mark.parametrize("nseg", [1, 3, 9])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_gradients_any_window_long_rows_in_segments(lb, oracle, nseg, dtype):
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(1, 70, 16, 601, seed=9420 + nseg, dtype=dtype, with_dout=True)
+    lb.lbscan_set_option("segments", nseg)
+    try:
+        _run_bwd(lb, oracle, s, window=3, dtype=dtype)
+        _run_bwd(lb, oracle, s, window=10, dtype=dtype, reverse=True)
+    finally:
+        lb.lbscan_set_option("segments", 0)
+
+
+def test_gradients_any_window_without_optionals_and_default_segments(lb, oracle):
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(1, 64, 16, 3000, seed=9430, with_dout=True, with_z=False)
+    s["Dskip"] = None
+    s["delta_bias"] = None
+    _run_bwd(lb, oracle, s, window=6)

@@ -133,12 +133,14 @@ def test_window_covering_short_row(lb, oracle):
     _run_fwd(lb, oracle, s, window=1000)
 
 
-def test_backward_of_a_window_without_fused_kernel_is_an_error(lb):
+def test_backward_of_a_long_window_without_fused_kernel_is_an_error(lb):
+    """The backward pass of window lengths without a fused kernel covers windows of
+    up to 16 tokens."""
     from gpu_util import fwd_inputs, to_device
     from paper_2506_15976_amd.inputs import make_inputs
     dev = to_device(make_inputs(1, 64, 16, 64, seed=6, with_dout=True), "fp32")
     with pytest.raises(lb.LbscanError) as ei:
-        lb.lbscan_bwd(**fwd_inputs(dev), dout=dev["dout"], window=3)
+        lb.lbscan_bwd(**fwd_inputs(dev), dout=dev["dout"], window=17)
     assert ei.value.code == -2
 
 
