@@ -28,9 +28,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # at half rate on this chip (measured), i.e. it takes two issue slots.
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
 # Issue slots per state update of rowlane_fwd_kernel, from SQ_INSTS_VALU and
-# SQ_INSTS_VALU_TRANS_F32 in profiles/lbscan_counters_vim_small.md (10.7 VALU instructions
-# incl. 1.3 transcendental).
-FWD_SLOTS_PER_STATE_UPDATE = 12.0
+# SQ_INSTS_VALU_TRANS_F32 in profiles/lbscan_counters_vim_small.md (10.4 VALU instructions
+# incl. 1.3 transcendental, which take two slots each).
+FWD_SLOTS_PER_STATE_UPDATE = 11.7
 FWD_KEYS = ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")
 
 # L2-to-fabric bytes per lbscan_fwd call from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
@@ -38,11 +38,11 @@ FWD_KEYS = ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")
 # same counter reads for a plain elementwise kernel that reads and writes 1 GiB
 # (bench.py --copy-calibration: FETCH_SIZE x2.0, WRITE_SIZE x1.0); profiles/ has the runs.
 MEASURED_TRAFFIC_BYTES = {
-    "vim_tiny": int((42457.3 * 2.0 + 26023.4) * 1024),
-    "vim_small": int((236066.0 * 2.0 + 97180.0) * 1024),
+    "vim_tiny": int((42431.9 * 2.0 + 25981.7) * 1024),
+    "vim_small": int((235351.2 * 2.0 + 97353.0) * 1024),
     # summary launch + carry chain + full pass
-    "hires_4096": int(((129130.2 + 76568.6 + 2356.6) * 2.0 + 59211.0 + 3265.0 + 3072.0) * 1024),
-    "wsi_bag": int(((116332.2 + 82080.3 + 12829.1) * 2.0 + 65553.0 + 3179.7 + 6078.9) * 1024),
+    "hires_4096": int(((128538.2 + 76416.9 + 2357.1) * 2.0 + 58338.4 + 3264.9 + 3072.0) * 1024),
+    "wsi_bag": int(((116340.4 + 82075.8 + 12812.9) * 2.0 + 65553.3 + 3179.7 + 6014.8) * 1024),
 }
 
 
