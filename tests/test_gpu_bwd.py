@@ -214,3 +214,14 @@ def test_gradients_any_window_without_optionals_and_default_segments(lb, oracle)
     s["Dskip"] = None
     s["delta_bias"] = None
     _run_bwd(lb, oracle, s, window=6)
+
+
+def test_full_size_gradients_bf16_4096_tokens(lb, oracle):
+    """The 4096-token bf16 shape is a forward workload; its gradients are checked at
+    full size too (M = 8 kernels, rows cut into segments, bf16 storage)."""
+    from paper_2506_15976_amd.inputs import BASE_SEED, WORKLOADS, make_inputs
+    w = WORKLOADS["hires_4096"]
+    s = make_inputs(w["batch"], w["dim"], w["dstate"], w["seqlen"], seed=BASE_SEED + 53, dtype="bf16",
+                    with_dout=True)
+    errs = _run_bwd(lb, oracle, s, window=w["window"], dtype="bf16")
+    print({k: f"{v:.2e}" for k, v in errs.items()})
