@@ -91,6 +91,41 @@ def test_workspace_sizes(lib):
     assert lib.lbscan_workspace_bytes(ctypes.byref(a), WS_BIDIR) == 2 * 8 * 10 * 4
 
 
+def test_workspace_sizes_follow_the_launch_plan(lib):
+    """Host logic only: scratch sizes for uncut rows, rows cut into segments, window
+    lengths without a fused kernel, and the saved-state buffer."""
+    from paper_2506_15976_amd.binding import LbscanArgs, WS_BWD, WS_FWD, WS_SAVED
+    B, D, N, L = 2, 128, 16, 200
+    a = LbscanArgs()
+    a.batch, a.dim, a.dstate, a.seqlen, a.window = B, D, N, L, 4
+    ws = lambda which: lib.lbscan_workspace_bytes(ctypes.byref(a), which)
+    rows, tiles16 = B * D, (L + 15) // 16
+    try:
+        assert lib.lbscan_set_option(b"segments", 1) == 0
+        assert ws(WS_FWD) == 0
+        assert ws(WS_SAVED) == tiles16 * rows * N * 4
+        assert ws(WS_BWD) == (tiles16 * rows * N + tiles16 * rows) * 4          # checkpoints + dt sums
+        a.dtype = 1                                                            # bf16: + fp32 dBm, dCm
+        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + 2 * B * N * L) * 4
+        a.window = 3                                                           # no fused kernel
+        assert ws(WS_FWD) == rows * L * 4                                      # fp32 first-pass result
+        assert ws(WS_SAVED) == 0
+        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + 2 * B * N * L + 3 * rows * L) * 4
+        a.window = 17
+        assert ws(WS_BWD) == 0                                                 # unsupported
+        a.dtype, a.window = 0, 4
+        assert lib.lbscan_set_option(b"segments", 3) == 0                      # 7 tiles of 32 -> 3 + 3 + 1
+        assert ws(WS_FWD) == 3 * rows * (N + 1) * 4
+        assert ws(WS_SAVED) == 0
+        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + 3 * rows * (2 * N + 1)) * 4
+    finally:
+        assert lib.lbscan_set_option(b"segments", 0) == 0
+    assert lib.lbscan_set_option(b"segments", -1) != 0
+    assert lib.lbscan_set_option(b"waves_log2", 4) != 0
+    assert lib.lbscan_set_option(b"no_such_option", 0) != 0
+    assert lib.lbscan_set_option(None, 0) != 0
+
+
 def test_header_is_plain_c(tmp_path):
     """include/lbscan.h compiles as C99 on its own (no C++ or framework types)."""
     import subprocess
