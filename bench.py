@@ -81,8 +81,8 @@ def upload(s, dtype):
 def time_calls(calls, steps, warmup, per_launch=False):
     """Run `calls[i % len]()` warmup + steps times on the current stream.  Returns the
     average milliseconds per step from HIP events around the whole timed region and,
-    with per_launch, also the mean of per-launch durations from an event pair around
-    every launch (kernel time without the gaps between dependent launches)."""
+    with per_launch, also mean / median / min of per-launch durations from an event
+    pair around every launch (without the gaps between dependent launches)."""
     import torch
     for i in range(warmup):
         calls[i % len(calls)]()
@@ -103,7 +103,8 @@ def time_calls(calls, steps, warmup, per_launch=False):
         calls[i % len(calls)]()
         ev[i][1].record()
     torch.cuda.synchronize()
-    return region, sum(a.elapsed_time(b) for a, b in ev) / n
+    per = sorted(a.elapsed_time(b) for a, b in ev)
+    return region, {"mean": sum(per) / n, "median": per[n // 2], "min": per[0]}
 
 
 def main():
@@ -266,10 +267,21 @@ def main():
         for _ in range(reps):
             oracle.fwd(**sub, window=w["window"])
         per_call = (time.perf_counter() - t0) / reps
-        cpu = {"value": nb * w["seqlen"] / per_call, "unit": "tokens/s", "cores": oracle.num_threads(),
+        # the same loop on one core, on a smaller slice
+        threads = oracle.num_threads()
+        nb1 = max(1, nb // 8)
+        sub1 = {k: (v[:nb1] if isinstance(v, np.ndarray) and v.ndim == 3 else v) for k, v in host.items()}
+        oracle.set_num_threads(1)
+        t0 = time.perf_counter()
+        oracle.fwd(**sub1, window=w["window"])
+        one_core = time.perf_counter() - t0
+        oracle.set_num_threads(threads)
+        cpu = {"value": nb * w["seqlen"] / per_call, "unit": "tokens/s", "cores": threads,
                "kind": "oracle",
                "sample": f"fp64 oracle forward on {nb} of {w['batch']} batch entries of {a.workload}, "
-                         f"mean of {reps} calls, {per_call:.4f} s per call"}
+                         f"mean of {reps} calls, {per_call:.4f} s per call",
+               "one_core_value": nb1 * w["seqlen"] / one_core,
+               "one_core_sample": f"{nb1} batch entries, one call, {one_core:.3f} s"}
 
     line = {
         "metric": "lbscan_fwd_tokens_per_s", "value": tokens / (ms_fwd * 1e-3), "unit": "tokens/s",
@@ -281,7 +293,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": "rowlane_fwd_kernel", "algorithmic_bytes_per_launch": fwd_bytes,
-                     "launch_ms": ms_fwd, "launch_ms_event_pairs": ms_kernel},
+                     "launch_ms": ms_fwd, "launch_ms_event_pairs": ms_kernel["mean"],
+                     "launch_ms_median": ms_kernel["median"], "launch_ms_min": ms_kernel["min"]},
         "alu_bound": {"unit": "state updates/s",
                       "achieved": tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3),
                       "peak": VALU_PEAK_LANE_OPS / FWD_SLOTS_PER_STATE_UPDATE,
