@@ -31,6 +31,7 @@ VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
 # SQ_INSTS_VALU_TRANS_F32 in profiles/lbscan_counters_vim_small.md (10.4 VALU instructions
 # incl. 1.3 transcendental, which take two slots each).
 FWD_SLOTS_PER_STATE_UPDATE = 11.7
+FWD_VALU_PER_SU, FWD_TRANS_PER_SU = 9.1, 1.3
 FWD_KEYS = ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")
 
 # L2-to-fabric bytes per lbscan_fwd call from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
@@ -44,6 +45,21 @@ MEASURED_TRAFFIC_BYTES = {
     "hires_4096": int(((128538.2 + 76416.9 + 2357.1) * 2.0 + 58338.4 + 3264.9 + 3072.0) * 1024),
     "wsi_bag": int(((116340.4 + 82075.8 + 12812.9) * 2.0 + 65553.3 + 3179.7 + 6014.8) * 1024),
 }
+
+
+def alu_bound(su_per_s, rates):
+    """fp32 VALU issue bound of the forward kernel at its present instruction count:
+    FWD_VALU_PER_SU plain instructions and FWD_TRANS_PER_SU transcendental ones per
+    state update, priced at the nominal issue peak (transcendentals at half rate) or,
+    with measured rates, at what the probe kernels reached on this machine."""
+    if rates:
+        t = FWD_VALU_PER_SU / rates["fma"] + FWD_TRANS_PER_SU / rates["exp2"]
+        peak, how = 1.0 / t, "measured issue rates"
+    else:
+        peak, how = VALU_PEAK_LANE_OPS / FWD_SLOTS_PER_STATE_UPDATE, "nominal issue peak"
+    return {"unit": "state updates/s", "achieved": su_per_s, "peak": peak, "frac": su_per_s / peak,
+            "rates_lane_ops_per_s": rates,
+            "note": f"fp32 VALU issue bound of the forward kernel at its present instruction count, {how}"}
 
 
 def algorithmic_bytes(w, which="fwd"):
@@ -118,6 +134,9 @@ def main():
     ap.add_argument("--no-bwd", action="store_true", help="skip the backward-pass timing")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--alu-rates", action="store_true",
+                    help="measure the fp32 fma, exp2 and rcp issue rates with the library's probe kernels and "
+                         "use them for alu_bound instead of the nominal peak")
     ap.add_argument("--waves-log2", type=int, default=-1, help="force the state-split launch shape (tuning)")
     ap.add_argument("--segments", type=int, default=0, help="force the number of row segments (tuning)")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets to rotate over (0: enough for 640 MB)")
@@ -243,6 +262,17 @@ def main():
     ms_conv = time_calls(conv_calls, max(a.steps // 4, 1), max(a.warmup // 4, 1))
     conv_bytes = 2 * w["batch"] * w["dim"] * w["seqlen"] * (2 if w["dtype"] == "bf16" else 4)
 
+    # issue rates of the three instruction kinds the ALU bound is made of (lane-ops/s)
+    rates = None
+    if a.alu_rates:
+        blocks, iters = 256 * 8, 2000                       # 8 waves per SIMD, about a millisecond each
+        pout = torch.empty(blocks * 256, dtype=torch.float32, device="cuda:0")
+        rates = {}
+        for which, name in ((0, "fma"), (1, "exp2"), (2, "rcp")):
+            per_lane = lb.lbscan_probe_rate(which, blocks, iters, pout)
+            ms = time_calls([lambda which=which: lb.lbscan_probe_rate(which, blocks, iters, pout)], 10, 2)
+            rates[name] = per_lane * blocks * 256 / (ms * 1e-3)
+
     tokens = w["batch"] * w["seqlen"]
     # average launch duration over the timed region (includes the ~5 us gap between
     # dependent launches; an event pair per launch reads slightly more, a kernel trace less)
@@ -295,12 +325,7 @@ def main():
                      "kernel": "rowlane_fwd_kernel", "algorithmic_bytes_per_launch": fwd_bytes,
                      "launch_ms": ms_fwd, "launch_ms_event_pairs": ms_kernel["mean"],
                      "launch_ms_median": ms_kernel["median"], "launch_ms_min": ms_kernel["min"]},
-        "alu_bound": {"unit": "state updates/s",
-                      "achieved": tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3),
-                      "peak": VALU_PEAK_LANE_OPS / FWD_SLOTS_PER_STATE_UPDATE,
-                      "frac": tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3) /
-                              (VALU_PEAK_LANE_OPS / FWD_SLOTS_PER_STATE_UPDATE),
-                      "note": "fp32 VALU issue bound of the forward kernel at its present instruction count"},
+        "alu_bound": alu_bound(tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3), rates),
         "cpu_baseline": cpu,
         "speedup_vs_two_pass_bidir": ms_bidir / ms_fwd,
         "two_pass_bidir_ms": ms_bidir,

@@ -183,6 +183,14 @@ int lbscan_default_window(int32_t seqlen);
  * Returns LBSCAN_EINVAL for an unknown name or a value out of range. */
 int lbscan_set_option(const char *name, int value);
 
+/* Diagnostic for the benchmark's ALU bound (not part of the method): launches
+ * `blocks` workgroups of 256 lanes that each execute the returned number of
+ * dependent instructions per lane of one kind - which = 0: fp32 fma, 1: exp2
+ * (v_exp_f32), 2: reciprocal (v_rcp_f32) - in eight independent chains.  The caller
+ * times the launch.  out: device buffer of blocks * 256 floats (overwritten).
+ * Returns the instruction count per lane, or a negative LBSCAN_E* code. */
+long lbscan_probe_rate(int which, int blocks, int iters, float *out, void *hip_stream);
+
 const char *lbscan_strerror(int code);
 /* Text of the last HIP error seen by this thread ("" if none). */
 const char *lbscan_last_error(void);

@@ -21,6 +21,7 @@ EXPORTS = (
     "lbscan_fwd", "lbscan_bwd", "lbscan_bidir_fwd", "lbscan_workspace_bytes",
     "lbscan_default_window", "lbscan_strerror", "lbscan_last_error", "lbscan_version",
     "lbscan_set_option", "lbscan_bwd_state", "lbscan_conv1d_fwd", "lbscan_conv1d_bwd",
+    "lbscan_probe_rate",
 )
 
 
@@ -86,6 +87,8 @@ def load():
     lib.lbscan_conv1d_fwd.argtypes = [cp, vp]
     lib.lbscan_conv1d_bwd.restype = ctypes.c_int
     lib.lbscan_conv1d_bwd.argtypes = [cp] + [vp] * 5
+    lib.lbscan_probe_rate.restype = ctypes.c_long
+    lib.lbscan_probe_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
     lib.lbscan_workspace_bytes.restype = ctypes.c_size_t
     lib.lbscan_workspace_bytes.argtypes = [ap, ctypes.c_int]
     lib.lbscan_default_window.restype = ctypes.c_int
@@ -318,3 +321,14 @@ def lbscan_conv1d_bwd(x, weight, bias=None, *, dy, activation=True, reverse=Fals
                                   _ptr(g["dbias"]), _stream(stream))
     _check(rc, "lbscan_conv1d_bwd")
     return g
+
+
+def lbscan_probe_rate(which: int, blocks: int, iters: int, out, stream=None) -> int:
+    """Launch the issue-rate probe (see include/lbscan.h); returns the instruction
+    count per lane.  out: float32 device tensor of blocks * 256 elements."""
+    if out.numel() < blocks * 256 or not out.is_cuda or not out.is_contiguous():
+        raise LbscanError(EINVAL, "out must be a contiguous device tensor of blocks * 256 floats")
+    n = load().lbscan_probe_rate(int(which), int(blocks), int(iters), _ptr(out), _stream(stream))
+    if n < 0:
+        _check(int(n), "lbscan_probe_rate")
+    return int(n)

@@ -318,6 +318,13 @@ size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
     }
 }
 
+long lbscan_probe_rate(int which, int blocks, int iters, float* out, void* hip_stream)
+{
+    if (which < 0 || which > 2 || blocks <= 0 || iters <= 0 || !out || !aligned4(out)) return LBSCAN_EINVAL;
+    hipError_t e = lbscan::launch_probe(which, blocks, iters, out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? lbscan::probe_ops_per_lane(iters) : hip_fail(e, "lbscan_probe_rate");
+}
+
 int lbscan_default_window(int32_t seqlen)
 {
     if (seqlen > 256) return 16;

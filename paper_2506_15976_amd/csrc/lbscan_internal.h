@@ -168,6 +168,12 @@ size_t bwd_workspace_bytes(const FwdParams& f, int local_window = 0);
 hipError_t launch_conv1d_fwd(const ConvParams& p, hipStream_t stream);
 hipError_t launch_conv1d_bwd(const ConvParams& p, hipStream_t stream);
 
+// Issue-rate probes (lbscan_probe.hip): `blocks` blocks of 256 lanes, every lane
+// executing probe_ops_per_lane(iters) instructions of kind which (0 fp32 fma, 1
+// exp2, 2 rcp); out holds blocks * 256 floats.
+hipError_t launch_probe(int which, int blocks, int iters, float* out, hipStream_t stream);
+long probe_ops_per_lane(int iters);
+
 // Chains the per-segment summaries into the states entering each segment
 // (lbscan_carry.hip): carry[s] <- exclusive scan over s of (exp(A*dsum), carry),
 // started from p.h0 (zeros when null).
