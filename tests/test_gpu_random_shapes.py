@@ -1,6 +1,8 @@
 """A fixed, seeded sweep of random valid shapes and options through the C ABI:
 forward and backward against the fp64 oracle.  The list is deterministic (same
 cases every run); it exists to cover combinations the hand-picked cases miss."""
+import os
+
 import numpy as np
 import pytest
 
@@ -16,8 +18,10 @@ def lb():
     return pkg
 
 
-def _cases(n=36):
-    r = np.random.default_rng(20250615)
+def _cases():
+    # LBSCAN_RANDOM_CASES / LBSCAN_RANDOM_SEED widen or move the sweep for a one-off run
+    n = int(os.environ.get("LBSCAN_RANDOM_CASES", "36"))
+    r = np.random.default_rng(int(os.environ.get("LBSCAN_RANDOM_SEED", "20250615")))
     out = []
     for i in range(n):
         out.append(dict(
