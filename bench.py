@@ -143,7 +143,7 @@ def main():
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (the scan needs no cross-GPU exchange in "
-              "forward; see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+              "forward: rows shard over batch or channels); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
