@@ -39,11 +39,11 @@ FWD_KEYS = ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")
 # same counter reads for a plain elementwise kernel that reads and writes 1 GiB
 # (bench.py --copy-calibration: FETCH_SIZE x2.0, WRITE_SIZE x1.0); profiles/ has the runs.
 MEASURED_TRAFFIC_BYTES = {
-    "vim_tiny": int((42431.9 * 2.0 + 25981.7) * 1024),
-    "vim_small": int((235351.2 * 2.0 + 97353.0) * 1024),
+    "vim_tiny": int((42414.4 * 2.0 + 25978.7) * 1024),
+    "vim_small": int((234641.4 * 2.0 + 97432.1) * 1024),
     # summary launch + carry chain + full pass
-    "hires_4096": int(((128538.2 + 76416.9 + 2357.1) * 2.0 + 58338.4 + 3264.9 + 3072.0) * 1024),
-    "wsi_bag": int(((116340.4 + 82075.8 + 12812.9) * 2.0 + 65553.3 + 3179.7 + 6014.8) * 1024),
+    "hires_4096": int(((128629.7 + 73254.8 + 2357.1) * 2.0 + 58316.8 + 3265.7 + 3072.0) * 1024),
+    "wsi_bag": int(((116334.2 + 82034.2 + 12812.9) * 2.0 + 65552.7 + 3179.2 + 6014.8) * 1024),
 }
 
 
