@@ -11,11 +11,10 @@
  *   - discretisation:            Sec. 3.1, Eq. 3 and Algorithm 1 (softplus with
  *                                additive Delta parameter, A-bar, B-bar)
  *   - global forward recurrence: Sec. 3.1, Eq. 1-2
- *   - local backward recurrence: Sec. 3.2, Eq. 7, in the order of Algorithm 1's
- *                                second (right-to-left) loop, including its
- *                                trick of carrying the backward state without
- *                                the current B-bar*x
- *   - combination and output:    Sec. 3.2, Eq. 8; gate: Algorithm 1 (SiLU(z))
+ *   - local backward recurrence: Sec. 3.2, Eq. 7: the state with its own input
+ *                                term, restarted at the last step of each window
+ *   - combination and output:    Sec. 3.2, Eq. 8: h = f + (h^b - B-bar x), the
+ *                                input term counted once; gate: Algorithm 1 (SiLU(z))
  *   - global bi-directional scan (the comparison method): Sec. 3.1, Eq. 4-6
  *   - gradients: the paper gives no formulas (Appendix B reports only
  *     throughput); lbscan_ref_bwd is the reverse-mode derivative of the
@@ -28,10 +27,12 @@
  *     f_t is used.
  *   - Eq. 7/8 print "B^f x_t" without the bar; Algorithm 1 uses B-bar, and the
  *     text says it is the same term as in Eq. 1, so B-bar_t x_t is meant.
- *   - windows are [kM, kM+M-1] in 0-based time (Algorithm 1 resets when
+ *   - windows are [kM, kM+M-1] in 0-based time (Eq. 7 counts tokens from 1 and
+ *     restarts at t % M = 0; Algorithm 1 counts from 0 and restarts when
  *     (i+1) % M == 0); a ragged last window is an ordinary short window.
- *   - the backward step multiplies by A-bar of the destination step
- *     (Algorithm 1 uses A-bar[:, i] on the state carried from i+1).
+ *   - Eq. 4 and Eq. 7 print A-bar without a time index; the backward step
+ *     multiplies by A-bar of the step it arrives at (as Algorithm 1 does), which
+ *     makes the local backward scan the forward scan run right to left.
  *   - softplus(v) = v for v > 20 (relative effect < 3e-9), else log1p(exp(v)).
  *   - Algorithm 1 starts both states at zero.  The *_state entry points also
  *     accept a forward state h0 entering at the first step and return the
@@ -135,7 +136,8 @@ int lbscan_ref_fwd_state(const lbref_problem *p, const double *h0, double *out, 
         double *yr = out + row * L;
         double *dt = (double *)malloc(sizeof(double) * L);
         double *F = (double *)malloc(sizeof(double) * L);
-        if (!dt || !F) { fail = 1; free(dt); free(F); continue; }
+        double *HB = (double *)malloc(sizeof(double) * L);
+        if (!dt || !F || !HB) { fail = 1; free(dt); free(F); free(HB); continue; }
         row_timestep(p, d, draw, dt);
         const double Dd = p->Dskip ? p->Dskip[d] : 0.0;
         for (int t = 0; t < L; ++t) yr[t] = Dd * xr[t];
@@ -150,22 +152,27 @@ int lbscan_ref_fwd_state(const lbref_problem *p, const double *h0, double *out, 
                 F[t] = hf;
             }
             if (hT) hT[row * N + n] = hf;
-            /* local backward recurrence, Eq. 7, in Algorithm 1's order:
-               decay (or reset at the last step of a window), use, then add
-               the current input term for the next (earlier) step. */
-            double hb = 0.0;
+            /* local backward recurrence, Eq. 7: inside every window [kM, kM+M-1]
+               (a ragged last window ends at L-1) the state with its own input
+               term is  hb_t = u_t  at the window's last step and
+               hb_t = abar_t hb_{t+1} + u_t  before it. */
             for (int t = L - 1; t >= 0; --t) {
-                if ((t + 1) % M == 0) hb = 0.0;
-                else hb = exp(dt[t] * a) * hb;
-                yr[t] += Cn[t] * (F[t] + hb);       /* Eq. 8 */
-                hb += dt[t] * Bn[t] * xr[t];
+                const double ut = dt[t] * Bn[t] * xr[t];
+                const int last = ((t + 1) % M == 0) || (t == L - 1);
+                HB[t] = last ? ut : exp(dt[t] * a) * HB[t + 1] + ut;
+            }
+            /* combination, Eq. 8: the input term sits in both states and is
+               counted once, h_t = f_t + (hb_t - u_t);  y_t = C_t h_t (+ D x_t above) */
+            for (int t = 0; t < L; ++t) {
+                const double ut = dt[t] * Bn[t] * xr[t];
+                yr[t] += Cn[t] * (F[t] + (HB[t] - ut));
             }
         }
         if (p->z) {
             const double *zr = p->z + row * L;
             for (int t = 0; t < L; ++t) yr[t] *= zr[t] * sigmoid64(zr[t]);
         }
-        free(dt); free(F);
+        free(dt); free(F); free(HB);
     }
     return fail ? -2 : 0;
 }

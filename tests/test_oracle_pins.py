@@ -263,6 +263,82 @@ def test_ragged_tail_equals_zero_padding(oracle):
     np.testing.assert_allclose(padded[..., :L], base, rtol=1e-13, atol=1e-15)
 
 
+# ------------------------------------------- the time step above and below 20
+
+def _const_step_problem(v, L=9, seed=0):
+    """Every time step has delta + delta_bias = v exactly; A is small so that
+    abar stays away from zero at time steps near 20."""
+    r = np.random.default_rng(300 + seed)
+    B, D, N = 1, 2, 3
+    bias = np.array([0.5, -1.25])
+    return dict(
+        x=r.standard_normal((B, D, L)),
+        delta=np.broadcast_to((v - bias)[None, :, None], (B, D, L)).copy(),
+        A=-r.uniform(0.005, 0.02, size=(D, N)),
+        Bm=r.standard_normal((B, N, L)), Cm=r.standard_normal((B, N, L)),
+        Dskip=r.standard_normal(D), z=r.standard_normal((B, D, L)), delta_bias=bias)
+
+
+@pytest.mark.parametrize("v", [20.5, 25.0, 40.0])
+def test_softplus_is_identity_above_twenty(oracle, v):
+    """Algorithm 1's Delta line with the reading softplus(v) = v for v > 20: the
+    run with softplus on equals the run with softplus off bit for bit (and so do
+    the gradients, whose softplus factor is exactly 1 there)."""
+    p = _const_step_problem(v, seed=int(v))
+    assert np.all(p["delta"] + p["delta_bias"][None, :, None] == v)
+    on = oracle.fwd(**p, window=4, delta_softplus=True)
+    off = oracle.fwd(**p, window=4, delta_softplus=False)
+    assert np.array_equal(on, off)
+    dout = np.random.default_rng(5).standard_normal(p["x"].shape)
+    g_on = oracle.bwd(**p, dout=dout, window=4, delta_softplus=True)
+    g_off = oracle.bwd(**p, dout=dout, window=4, delta_softplus=False)
+    for k in g_on:
+        assert np.array_equal(g_on[k], g_off[k]), k
+
+
+@pytest.mark.parametrize("v", [19.0, 19.99, 20.0])
+def test_softplus_is_log1p_exp_up_to_twenty(oracle, v):
+    """At and below 20 the time step is log(1 + exp(v)) itself (no threshold in
+    this check): the output equals the unrolled sums fed with it, differs from
+    the softplus-off run, and ddelta carries the factor sigma(v) < 1."""
+    p = _const_step_problem(v, seed=int(v * 100))
+    sp = math.log1p(math.exp(v))
+    assert sp > v
+    on = oracle.fwd(**p, window=4, delta_softplus=True)
+    q = dict(p, delta=np.full_like(p["delta"], sp), delta_bias=None)
+    ref = _brute_force(q, 4, False)
+    np.testing.assert_allclose(on, ref, rtol=1e-13, atol=1e-14)
+    assert not np.array_equal(on, oracle.fwd(**p, window=4, delta_softplus=False))
+    dout = np.random.default_rng(6).standard_normal(p["x"].shape)
+    g_on = oracle.bwd(**p, dout=dout, window=4, delta_softplus=True)
+    g_lin = oracle.bwd(**q, dout=dout, window=4, delta_softplus=False)
+    sig = 1.0 / (1.0 + math.exp(-v))
+    assert sig < 1.0
+    np.testing.assert_allclose(g_on["ddelta"], g_lin["ddelta"] * sig, rtol=1e-13, atol=1e-300)
+    np.testing.assert_allclose(g_on["ddelta_bias"], g_lin["ddelta"].sum(axis=(0, 2)) * sig, rtol=1e-12)
+    # sigma(19) = 1 - 5.6e-9 is told apart from 1 at this tolerance
+    assert np.max(np.abs(g_on["ddelta"] - g_lin["ddelta"])) > 1e-10 * np.max(np.abs(g_lin["ddelta"]))
+
+
+@pytest.mark.parametrize("v", [18.0, 19.5, 20.5, 22.0])
+def test_time_step_gradients_by_central_differences_around_twenty(oracle, v):
+    p = _const_step_problem(v, L=7, seed=int(v * 10))
+    dout = np.random.default_rng(7).standard_normal(p["x"].shape)
+    g = oracle.bwd(**p, dout=dout, window=4, delta_softplus=True)
+    loss = lambda q: float(np.sum(dout * oracle.fwd(**q, window=4, delta_softplus=True)))
+    h = 1e-5
+    for name, gname in (("delta", "ddelta"), ("delta_bias", "ddelta_bias")):
+        arr = p[name]
+        scale = np.sqrt(np.mean(g[gname] ** 2))
+        for fi in range(0, arr.size, max(1, arr.size // 6)):
+            idx = np.unravel_index(fi, arr.shape)
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += h
+            lo[idx] -= h
+            fd = (loss(dict(p, **{name: hi})) - loss(dict(p, **{name: lo}))) / (2 * h)
+            assert abs(fd - g[gname][idx]) <= 1e-6 * max(abs(fd), scale), (name, idx, fd, g[gname][idx])
+
+
 # ----------------------------------------------------------------- gradients
 
 _GRAD_OF = dict(x="dx", delta="ddelta", z="dz", Bm="dBm", Cm="dCm", A="dA", Dskip="dDskip",
