@@ -134,9 +134,6 @@ def main():
     ap.add_argument("--no-bwd", action="store_true", help="skip the backward-pass timing")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
-    ap.add_argument("--alu-rates", action="store_true",
-                    help="measure the fp32 fma, exp2 and rcp issue rates with the library's probe kernels and "
-                         "use them for alu_bound instead of the nominal peak")
     ap.add_argument("--waves-log2", type=int, default=-1, help="force the state-split launch shape (tuning)")
     ap.add_argument("--segments", type=int, default=0, help="force the number of row segments (tuning)")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets to rotate over (0: enough for 640 MB)")
@@ -262,17 +259,7 @@ def main():
     ms_conv = time_calls(conv_calls, max(a.steps // 4, 1), max(a.warmup // 4, 1))
     conv_bytes = 2 * w["batch"] * w["dim"] * w["seqlen"] * (2 if w["dtype"] == "bf16" else 4)
 
-    # issue rates of the three instruction kinds the ALU bound is made of (lane-ops/s)
     rates = None
-    if a.alu_rates:
-        blocks, iters = 256 * 8, 2000                       # 8 waves per SIMD, about a millisecond each
-        pout = torch.empty(blocks * 256, dtype=torch.float32, device="cuda:0")
-        rates = {}
-        for which, name in ((0, "fma"), (1, "exp2"), (2, "rcp")):
-            per_lane = lb.lbscan_probe_rate(which, blocks, iters, pout)
-            ms = time_calls([lambda which=which: lb.lbscan_probe_rate(which, blocks, iters, pout)], 10, 2)
-            rates[name] = per_lane * blocks * 256 / (ms * 1e-3)
-
     tokens = w["batch"] * w["seqlen"]
     # average launch duration over the timed region (includes the ~5 us gap between
     # dependent launches; an event pair per launch reads slightly more, a kernel trace less)

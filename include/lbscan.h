@@ -28,8 +28,9 @@
  * Ownership: every data pointer is a caller-owned DEVICE pointer.  The library
  * never allocates, frees or synchronises; it enqueues work on the HIP stream
  * passed in (a hipStream_t cast to void*, NULL = default stream) and returns.
- * Outputs are fully overwritten.  Calls are re-entrant; the only global state
- * is a thread-local last-error string and the options of lbscan_set_option.
+ * Outputs are fully overwritten.  Calls are re-entrant as long as
+ * lbscan_set_option is not called concurrently: the only global state is a
+ * thread-local last-error string and the two process-wide tuning options.
  *
  * Errors: 0 on success, a negative LBSCAN_E* code otherwise; nothing is
  * enqueued when an error is returned before launch.
@@ -56,12 +57,17 @@ extern "C" {
 #define LBSCAN_MAX_DSTATE 16
 
 typedef struct lbscan_args {
-    int32_t batch, dim, dstate, seqlen;  /* B, D, N, L; any may be 0 (then nothing is done)   */
-    int32_t window;           /* M >= 1.  M in {1,2,4,8,16} (and any M >= L when L <= 16) runs
-                                 the fused single-pass kernels, forward and backward.  Any other
-                                 M runs as two passes over HBM each way (the plain scan with
-                                 window 1, then the local backward part): lbscan_fwd for every
-                                 M, lbscan_bwd for M <= 16 (LBSCAN_EUNSUPPORTED beyond) */
+    int32_t batch, dim, dstate, seqlen;  /* B, D, N, L.  B, D or L may be 0: nothing is computed
+                                            (the state passes through, reduced gradients are
+                                            zero).  N = 0 with B*D*L > 0 is LBSCAN_EUNSUPPORTED
+                                            (the result would be Dskip x SiLU(z); no kernel) */
+    int32_t window;           /* M >= 1, any value (Sec. 3.2 leaves the window length free;
+                                 M >= L is one window).  lbscan_fwd: M in {1,2,4,8,16} (and any
+                                 M >= L when L <= 16) runs one fused pass, any other M two
+                                 passes over HBM (the plain scan with window 1, then the local
+                                 backward part).  lbscan_bwd: one backward kernel for every M;
+                                 when 16 is not a multiple of M its checkpoint pass also reads
+                                 dout, z, Cm and needs N floats more scratch per 16 tokens */
     int32_t dtype;            /* LBSCAN_FP32 or LBSCAN_BF16: storage type of the (B,D,L) and
                                  (B,N,L) tensors; arithmetic is fp32 either way                */
     int32_t delta_softplus;   /* 0/1: apply softplus to delta + delta_bias (Algorithm 1)      */
@@ -111,7 +117,9 @@ int lbscan_fwd(const lbscan_args *args, void *hip_stream);
  * (fwd_args->y is not read; fwd_args->saved_state, if given, must have been filled
  * by lbscan_fwd on the same inputs).  dout is the upstream gradient of out.  dz may be
  * NULL iff fwd_args->z is NULL.  dDskip / ddelta_bias may be NULL iff the
- * corresponding input is NULL.  All outputs are overwritten (not accumulated). */
+ * corresponding input is NULL.  All outputs are overwritten (not accumulated).
+ * dBm and dCm are summed in a fixed order (the same bits on every run); dA, dDskip
+ * and ddelta_bias use fp32 atomics and may differ in their last bits between runs. */
 int lbscan_bwd(const lbscan_args *fwd_args, const void *dout,
                void *dx, void *ddelta, void *dz,
                void *dBm, void *dCm,
@@ -173,6 +181,10 @@ int lbscan_default_window(int32_t seqlen);
 
 /* Process-wide launch-shape override, for tuning and for tests that must reach
  * every kernel variant; results do not depend on it beyond rounding order.
+ * NOT thread-safe with respect to the other entry points: "segments" changes what
+ * lbscan_workspace_bytes returns and what the calls expect, so set options before
+ * other threads query sizes or launch, never between a thread's size query and its
+ * call.
  *   "waves_log2": -1 (default) lets the library choose over how many waves of
  *                 a block the N states of a row are split; 0..3 forces 1, 2, 4
  *                 or 8 (clamped to what the state size allows).
@@ -182,14 +194,6 @@ int lbscan_default_window(int32_t seqlen);
  *                 changes lbscan_workspace_bytes: query after setting it.
  * Returns LBSCAN_EINVAL for an unknown name or a value out of range. */
 int lbscan_set_option(const char *name, int value);
-
-/* Diagnostic for the benchmark's ALU bound (not part of the method): launches
- * `blocks` workgroups of 256 lanes that each execute the returned number of
- * dependent instructions per lane of one kind - which = 0: fp32 fma, 1: exp2
- * (v_exp_f32), 2: reciprocal (v_rcp_f32) - in eight independent chains.  The caller
- * times the launch.  out: device buffer of blocks * 256 floats (overwritten).
- * Returns the instruction count per lane, or a negative LBSCAN_E* code. */
-long lbscan_probe_rate(int which, int blocks, int iters, float *out, void *hip_stream);
 
 const char *lbscan_strerror(int code);
 /* Text of the last HIP error seen by this thread ("" if none). */

@@ -21,7 +21,6 @@ EXPORTS = (
     "lbscan_fwd", "lbscan_bwd", "lbscan_bidir_fwd", "lbscan_workspace_bytes",
     "lbscan_default_window", "lbscan_strerror", "lbscan_last_error", "lbscan_version",
     "lbscan_set_option", "lbscan_bwd_state", "lbscan_conv1d_fwd", "lbscan_conv1d_bwd",
-    "lbscan_probe_rate",
 )
 
 
@@ -87,8 +86,6 @@ def load():
     lib.lbscan_conv1d_fwd.argtypes = [cp, vp]
     lib.lbscan_conv1d_bwd.restype = ctypes.c_int
     lib.lbscan_conv1d_bwd.argtypes = [cp] + [vp] * 5
-    lib.lbscan_probe_rate.restype = ctypes.c_long
-    lib.lbscan_probe_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
     lib.lbscan_workspace_bytes.restype = ctypes.c_size_t
     lib.lbscan_workspace_bytes.argtypes = [ap, ctypes.c_int]
     lib.lbscan_default_window.restype = ctypes.c_int
@@ -184,15 +181,38 @@ def lbscan_version() -> str:
     return load().lbscan_version().decode()
 
 
-def _workspace_for(args, which, like):
+def _workspace_for(args, which, like, stream=None):
+    """Scratch for one call.  It is allocated from torch's caching allocator on the
+    current stream; when the call runs on another stream the block is tied to that
+    stream as well, so that it is not handed out again while the kernels use it."""
     import torch
     need = lbscan_workspace_bytes(args, which)
     if need == 0:
         return None
     ws = torch.empty((need + 3) // 4, dtype=torch.float32, device=like.device)
+    _tie_to_stream(stream, ws)
     args.workspace = ws.data_ptr()
     args.workspace_bytes = ws.numel() * 4
     return ws
+
+
+def _tie_to_stream(stream, *tensors):
+    """Tensors this binding allocated (current stream) and hands to kernels that run
+    on `stream`: record the use, so that the caching allocator waits for it."""
+    if stream is None:
+        return
+    for t in tensors:
+        if t is not None:
+            t.record_stream(stream)
+
+
+def _check_like(name, t, like):
+    """Gradient / output tensors handed in by the caller: same shape, dtype, device
+    kind and layout as the tensor they belong to."""
+    if (tuple(t.shape) != tuple(like.shape) or t.dtype != like.dtype or not t.is_cuda
+            or not t.is_contiguous()):
+        raise LbscanError(EINVAL, f"{name} must be a contiguous device tensor of shape "
+                                  f"{tuple(like.shape)} and dtype {like.dtype}")
 
 
 def lbscan_saved_state(x, A, *, window):
@@ -218,7 +238,8 @@ def lbscan_fwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, wind
     a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
                   delta_softplus=delta_softplus, reverse=reverse, y=y, saved_state=saved_state,
                   h0=h0, hT=hT)
-    ws = _workspace_for(a, WS_FWD, x)
+    ws = _workspace_for(a, WS_FWD, x, stream)
+    _tie_to_stream(stream, y if out is None else None, hT)
     _check(load().lbscan_fwd(ctypes.byref(a), _stream(stream)), "lbscan_fwd")
     del ws
     return (y, hT) if return_state else y
@@ -236,7 +257,8 @@ def lbscan_bidir_fwd(set_f: dict, set_b: dict, *, out=None, stream=None):
                          s.get("delta_bias"), window=1,
                          delta_softplus=s.get("delta_softplus", True), y=yy)
     af, ab = mk(set_f, y), mk(set_b, None)
-    ws = _workspace_for(af, WS_BIDIR, y)
+    ws = _workspace_for(af, WS_BIDIR, y, stream)
+    _tie_to_stream(stream, y if out is None else None)
     _check(load().lbscan_bidir_fwd(ctypes.byref(af), ctypes.byref(ab), _stream(stream)),
            "lbscan_bidir_fwd")
     del ws
@@ -253,8 +275,7 @@ def lbscan_bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout
     import torch
     a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
                   delta_softplus=delta_softplus, reverse=reverse, saved_state=saved_state, h0=h0)
-    if tuple(dout.shape) != tuple(x.shape) or dout.dtype != x.dtype or not dout.is_contiguous():
-        raise LbscanError(EINVAL, "dout must match x")
+    _check_like("dout", dout, x)
     g = dict(
         dx=torch.empty_like(x), ddelta=torch.empty_like(x),
         dz=torch.empty_like(x) if z is not None else None,
@@ -263,7 +284,8 @@ def lbscan_bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout
         dDskip=torch.empty_like(Dskip) if Dskip is not None else None,
         ddelta_bias=torch.empty_like(delta_bias) if delta_bias is not None else None,
     )
-    ws = _workspace_for(a, WS_BWD, x)
+    ws = _workspace_for(a, WS_BWD, x, stream)
+    _tie_to_stream(stream, *g.values())
     if h0 is None and dhT is None:
         rc = load().lbscan_bwd(ctypes.byref(a), _ptr(dout), _ptr(g["dx"]), _ptr(g["ddelta"]),
                                _ptr(g["dz"]), _ptr(g["dBm"]), _ptr(g["dCm"]), _ptr(g["dA"]),
@@ -275,6 +297,7 @@ def lbscan_bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout
                                 or not dhT.is_cuda or not dhT.is_contiguous()):
             raise LbscanError(EINVAL, f"dhT must be a contiguous float32 device tensor of shape {shape}")
         g["dh0"] = torch.empty(shape, dtype=torch.float32, device=x.device)
+        _tie_to_stream(stream, g["dh0"])
         rc = load().lbscan_bwd_state(ctypes.byref(a), _ptr(dout), _ptr(dhT), _ptr(g["dx"]),
                                      _ptr(g["ddelta"]), _ptr(g["dz"]), _ptr(g["dBm"]), _ptr(g["dCm"]),
                                      _ptr(g["dA"]), _ptr(g["dDskip"]), _ptr(g["ddelta_bias"]),
@@ -303,7 +326,10 @@ def lbscan_conv1d_fwd(x, weight, bias=None, *, activation=True, reverse=False, o
     """y = SiLU(depthwise causal conv of x along the last axis) (see include/lbscan.h).
     x (B,D,L), weight (D,K) fp32 with K <= 4, bias (D) fp32."""
     import torch
+    if out is not None:
+        _check_like("out", out, x)
     y = torch.empty_like(x) if out is None else out
+    _tie_to_stream(stream, y if out is None else None)
     a = _conv_args(x, weight, bias, activation, reverse, y)
     _check(load().lbscan_conv1d_fwd(ctypes.byref(a), _stream(stream)), "lbscan_conv1d_fwd")
     return y
@@ -312,23 +338,12 @@ def lbscan_conv1d_fwd(x, weight, bias=None, *, activation=True, reverse=False, o
 def lbscan_conv1d_bwd(x, weight, bias=None, *, dy, activation=True, reverse=False, stream=None):
     """Gradients of lbscan_conv1d_fwd: dict with dx, dweight, dbias (None without bias)."""
     import torch
-    if tuple(dy.shape) != tuple(x.shape) or dy.dtype != x.dtype or not dy.is_contiguous():
-        raise LbscanError(EINVAL, "dy must match x")
+    _check_like("dy", dy, x)
     a = _conv_args(x, weight, bias, activation, reverse)
     g = dict(dx=torch.empty_like(x), dweight=torch.empty_like(weight),
              dbias=torch.empty_like(bias) if bias is not None else None)
+    _tie_to_stream(stream, *g.values())
     rc = load().lbscan_conv1d_bwd(ctypes.byref(a), _ptr(dy), _ptr(g["dx"]), _ptr(g["dweight"]),
                                   _ptr(g["dbias"]), _stream(stream))
     _check(rc, "lbscan_conv1d_bwd")
     return g
-
-
-def lbscan_probe_rate(which: int, blocks: int, iters: int, out, stream=None) -> int:
-    """Launch the issue-rate probe (see include/lbscan.h); returns the instruction
-    count per lane.  out: float32 device tensor of blocks * 256 elements."""
-    if out.numel() < blocks * 256 or not out.is_cuda or not out.is_contiguous():
-        raise LbscanError(EINVAL, "out must be a contiguous device tensor of blocks * 256 floats")
-    n = load().lbscan_probe_rate(int(which), int(blocks), int(iters), _ptr(out), _stream(stream))
-    if n < 0:
-        _check(int(n), "lbscan_probe_rate")
-    return int(n)

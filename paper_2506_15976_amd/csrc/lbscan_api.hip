@@ -39,6 +39,8 @@ int check_args_sizes(const lbscan_args* a, bool* empty)
     if (a->reverse != 0 && a->reverse != 1) return LBSCAN_EINVAL;
     if (a->seqlen > (1 << 24)) return LBSCAN_EUNSUPPORTED;   // 64 rows * L is indexed in 32 bits
     if ((long)a->batch * a->dim * a->seqlen == 0) *empty = true;
+    // a state size of zero with steps to take (y = Dskip x SiLU(z)) has no kernel
+    if (!*empty && a->dstate == 0) return LBSCAN_EUNSUPPORTED;
     return LBSCAN_OK;
 }
 
@@ -48,7 +50,7 @@ int check_args(const lbscan_args* a, bool need_y, bool* empty)
     int rc = check_args_sizes(a, empty);
     if (rc != LBSCAN_OK || *empty) return rc;
     if (!a->x || !a->delta || (need_y && !a->y)) return LBSCAN_EINVAL;
-    if (a->dstate > 0 && (!a->A || !a->Bm || !a->Cm)) return LBSCAN_EINVAL;
+    if (!a->A || !a->Bm || !a->Cm) return LBSCAN_EINVAL;
     const void* ptrs[] = {a->x, a->delta, a->Bm, a->Cm, a->z, a->A, a->Dskip, a->delta_bias, a->y,
                           a->h0, a->hT};
     for (const void* p : ptrs)
@@ -80,7 +82,7 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     p.force_waves_log2 = tuning_waves_log2();
     p.force_nseg = tuning_nseg();
     p.nseg = 1; p.seg_tiles = 0; p.summary_only = 0; p.carry = nullptr; p.dsum = nullptr;
-    p.ckpt = nullptr; p.cum = nullptr; p.dout = nullptr; p.psi = nullptr;
+    p.ckpt = nullptr; p.cum = nullptr; p.dout = nullptr; p.psi = nullptr; p.gck = nullptr;
     p.h0 = a->h0; p.hT = a->hT;
     p.generic_window = 0; p.seg_tokens = 0;
     return p;
@@ -227,17 +229,13 @@ int lbscan_bwd_state(const lbscan_args* a, const void* dout, const float* dhT,
     const void* ptrs[] = {dout, dx, ddelta, dz, dBm, dCm, dA, dDskip, ddelta_bias, dhT, dh0};
     for (const void* q : ptrs)
         if (q && !aligned4(q)) return LBSCAN_EINVAL;
-    int M = effective_window(a->window, a->seqlen);
-    int local_window = 0;
-    if (M == 0) {
-        // no fused kernel for this window length: the fused kernel with window 1, then
-        // the local backward part by a kernel of its own (windows up to one tile)
-        local_window = a->window < a->seqlen ? a->window : a->seqlen;
-        if (local_window > lbscan::kTileTokens) return LBSCAN_EUNSUPPORTED;
-        M = 1;
-    }
+    // one backward kernel covers every window length (1, 2, 4 with a compiled window
+    // structure, all others with run-time window masks); a window that covers the
+    // whole row is the same as any longer one
+    const int fwdM = effective_window(a->window, a->seqlen);
+    const int M = fwdM ? fwdM : (a->window < a->seqlen ? a->window : a->seqlen);
     lbscan::FwdParams f = to_params(a, M);
-    const size_t need = lbscan::bwd_workspace_bytes(f, local_window);
+    const size_t need = lbscan::bwd_workspace_bytes(f);
     if (need && (!a->workspace || a->workspace_bytes < need || !aligned4(a->workspace)))
         return LBSCAN_EWORKSPACE;
     lbscan::BwdParams p;
@@ -246,19 +244,18 @@ int lbscan_bwd_state(const lbscan_args* a, const void* dout, const float* dhT,
     p.x = f.x; p.delta = f.delta; p.Bm = f.Bm; p.Cm = f.Cm; p.z = f.z;
     p.A = f.A; p.Dskip = f.Dskip; p.bias = f.bias;
     p.dout = dout; p.dx = dx; p.ddelta = ddelta; p.dz = a->z ? dz : nullptr;
-    p.dBacc = nullptr; p.dCacc = nullptr;
+    p.dBpart = nullptr;
     p.dA = dA; p.dDskip = a->Dskip ? dDskip : nullptr; p.dbias = a->delta_bias ? ddelta_bias : nullptr;
     p.ckpt = nullptr; p.nseg = 1; p.seg_tiles = 0; p.cum = nullptr; p.carry = nullptr; p.psi_in = nullptr;
-    p.dh0 = dh0;
-    p.part_dx = nullptr; p.part_ddelta = nullptr; p.part_dz = nullptr;
+    p.dh0 = dh0; p.gck = nullptr;
     f.hT = nullptr;
     const float* saved = nullptr;
-    if (a->saved_state && local_window == 0) {
+    if (a->saved_state && fwdM != 0) {
         const size_t sneed = lbscan::saved_state_bytes(f);
         if (sneed && (a->saved_state_bytes < sneed || !aligned4(a->saved_state))) return LBSCAN_EWORKSPACE;
         if (sneed) saved = static_cast<const float*>(a->saved_state);
     }
-    hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, saved, dhT, local_window, s);
+    hipError_t e = lbscan::launch_bwd(f, p, dBm, dCm, a->workspace, saved, dhT, s);
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_bwd");
 }
 
@@ -298,10 +295,8 @@ size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
         if (which == LBSCAN_WS_FWD)
             return lbscan::fwd_generic_workspace_bytes(to_params(a, a->window < a->seqlen ? a->window : a->seqlen));
         if (which == LBSCAN_WS_SAVED) return 0;
-        if (which == LBSCAN_WS_BWD) {
-            const int lw = a->window < a->seqlen ? a->window : a->seqlen;
-            return lw > lbscan::kTileTokens ? 0 : lbscan::bwd_workspace_bytes(to_params(a, 1), lw);
-        }
+        if (which == LBSCAN_WS_BWD)
+            return lbscan::bwd_workspace_bytes(to_params(a, a->window < a->seqlen ? a->window : a->seqlen));
         M = 1;
     }
     switch (which) {
@@ -316,13 +311,6 @@ size_t lbscan_workspace_bytes(const lbscan_args* a, int which)
                    lbscan::fwd_workspace_bytes(to_params(a, 1));
         default: return 0;
     }
-}
-
-long lbscan_probe_rate(int which, int blocks, int iters, float* out, void* hip_stream)
-{
-    if (which < 0 || which > 2 || blocks <= 0 || iters <= 0 || !out || !aligned4(out)) return LBSCAN_EINVAL;
-    hipError_t e = lbscan::launch_probe(which, blocks, iters, out, static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? lbscan::probe_ops_per_lane(iters) : hip_fail(e, "lbscan_probe_rate");
 }
 
 int lbscan_default_window(int32_t seqlen)

@@ -22,7 +22,7 @@ namespace {
 __global__ void __launch_bounds__(256)
 carry_chain_kernel(float* __restrict__ carry, const float* __restrict__ dsum,
                    const float* __restrict__ A, const float* __restrict__ init,
-                   int rows, int D, int N, int nseg, int reverse, int G)
+                   int rows, int D, int N, int nseg, int nsum, int reverse, int G)
 {
     const long npairs = (long)rows * N;
     const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -38,9 +38,12 @@ carry_chain_kernel(float* __restrict__ carry, const float* __restrict__ dsum,
         const bool on = ss < nseg;
         const int s = reverse ? nseg - 1 - (on ? ss : 0) : (on ? ss : 0);
         const long k = (long)s * npairs + i;
-        // lanes past the end of the chain hold the identity map
-        float e = on ? carry[k] : 0.0f;
-        float P = on ? fast_exp2(a2 * dsum[(long)s * rows + row]) : 1.0f;
+        // lanes past the end of the chain, and segments whose summary was not
+        // computed (ss >= nsum: the last one, which nothing follows), hold the
+        // identity map
+        const bool have = on && ss < nsum;
+        float e = have ? carry[k] : 0.0f;
+        float P = have ? fast_exp2(a2 * dsum[(long)s * rows + row]) : 1.0f;
         // inclusive scan: lane g ends with the composition of segments base..base+g
         for (int d = 1; d < G; d <<= 1) {
             const float Pp = __shfl_up(P, d, G), ep = __shfl_up(e, d, G);
@@ -131,7 +134,8 @@ hipError_t launch_carry_chain(const FwdParams& p, hipStream_t stream)
     const int G = chain_group(p.nseg);
     const unsigned blocks = (unsigned)((n * G + 255) / 256);
     hipLaunchKernelGGL(carry_chain_kernel, dim3(blocks), dim3(256), 0, stream,
-                       p.carry, p.dsum, p.A, p.h0, rows, p.dim, p.dstate, p.nseg, 0, G);
+                       p.carry, p.dsum, p.A, p.h0, rows, p.dim, p.dstate, p.nseg,
+                       p.ckpt ? p.nseg : p.nseg - 1, 0, G);
     return hipGetLastError();
 }
 
@@ -144,7 +148,7 @@ hipError_t launch_carry_chain_reverse(const FwdParams& p, float* buf, const floa
     const int G = chain_group(p.nseg);
     const unsigned blocks = (unsigned)((n * G + 255) / 256);
     hipLaunchKernelGGL(carry_chain_kernel, dim3(blocks), dim3(256), 0, stream,
-                       buf, p.dsum, p.A, init, rows, p.dim, p.dstate, p.nseg, 1, G);
+                       buf, p.dsum, p.A, init, rows, p.dim, p.dstate, p.nseg, p.nseg, 1, G);
     return hipGetLastError();
 }
 

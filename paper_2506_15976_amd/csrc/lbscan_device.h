@@ -15,28 +15,30 @@ __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float fast_log2(float v) { return __builtin_amdgcn_logf(v); }
 __device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
 
-// softplus(v) = log(1 + exp(v)), v > 20 -> v (Algorithm 1's Delta line).
-// The time step multiplies every state update, so it is kept to a few ulp:
-// the hardware log has an absolute, not relative, error near 1, hence
-//   e = exp(v) < 1/2 : log1p(e) = 2 atanh(s), s = e / (2 + e), odd series to s^9
-//   otherwise        : log(w) + (e - (w - 1)) / w with w = fl(1 + e), where the
-//                      second term restores the bits lost in rounding 1 + e.
+// softplus(v) = log(1 + exp(v)), v > 20 -> v (Algorithm 1's Delta line), and its
+// derivative sigma(v) = e / (1 + e) (1 above 20).  The time step multiplies every
+// state update, so it is kept to a few ulp, in one branch-free form for all v:
+// with e = exp(v) and w = fl(1 + e),
+//     log(1 + e) = log(w) + (e - (w - 1)) / w        (up to O(ulp^2)),
+// where the second term restores the bits lost when 1 + e was rounded (it is all
+// of the result for e < 2^-24).  v_log_f32 is accurate to ~1e-7 of its result
+// also for arguments next to 1 (measured on MI355X: 1.1e-7 over w - 1 in
+// [1e-7, 1]), so no series is needed there.  For v > 88 e overflows to inf and
+// the sum becomes NaN; the selects below discard it.
+__device__ __forceinline__ float softplus_f32(float v, float& dsoftplus)
+{
+    const float e = fast_exp2(v * kLog2e);
+    const float w = 1.0f + e;
+    const float rw = fast_rcp(w);
+    const float r = fmaf(fast_log2(w), kLn2, (e - (w - 1.0f)) * rw);
+    const bool lin = v > 20.0f;
+    dsoftplus = lin ? 1.0f : e * rw;
+    return lin ? v : r;
+}
 __device__ __forceinline__ float softplus_f32(float v)
 {
-    const float e = fast_exp2(fminf(v, 20.0f) * kLog2e);
-    float r;
-    if (e < 0.5f) {
-        const float s = e * fast_rcp(2.0f + e);
-        const float s2 = s * s;
-        float poly = fmaf(s2, 1.0f / 9.0f, 1.0f / 7.0f);
-        poly = fmaf(s2, poly, 1.0f / 5.0f);
-        poly = fmaf(s2, poly, 1.0f / 3.0f);
-        r = fmaf(2.0f * s, s2 * poly, 2.0f * s);
-    } else {
-        const float w = 1.0f + e;
-        r = fmaf(fast_log2(w), kLn2, (e - (w - 1.0f)) * fast_rcp(w));
-    }
-    return v > 20.0f ? v : r;
+    float unused;
+    return softplus_f32(v, unused);
 }
 
 __device__ __forceinline__ float sigmoid_f32(float v)
@@ -121,6 +123,31 @@ __device__ __forceinline__ Quad<T> quad_raw_checked(const T* __restrict__ base, 
         q.v[e] = (t == tc) ? v : zero_elem<T>();
     }
     return q;
+}
+
+// The same result as quad_raw_checked with ONE quad load, for rows of at least four
+// tokens that allow quad loads: the quad is loaded from the nearest position that
+// lies inside the row (ph clamped to [0, L-4]) and its elements are moved to where
+// they belong; elements whose token ph + e is outside [0, L) become zero.  Element
+// loads cost the texture-address unit one pass per element (a wave's 64 dwords sit
+// in up to 64 different sectors), which made the ragged last tile of a row as
+// expensive as a full one.
+template <typename T>
+__device__ __forceinline__ Quad<T> quad_raw_ragged(const T* __restrict__ base, long off, int ph, int L)
+{
+    const int phc = ph < 0 ? 0 : (ph > L - 4 ? L - 4 : ph);
+    const Quad<T> q = *reinterpret_cast<const Quad<T>*>(base + (off + (phc - ph)));
+    const int s = ph - phc;                       // wanted element e is loaded element e + s
+    Quad<T> r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int k = e + s;
+        T v = zero_elem<T>();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v = (k == j) ? q.v[j] : v;
+        r.v[e] = v;
+    }
+    return r;
 }
 
 template <typename T>

@@ -151,61 +151,74 @@ hipError_t launch_fwd_generic(FwdParams p, void* workspace, hipStream_t stream)
 
 namespace {
 
+// A window that straddles the start of a 16-token tile needs the part of the adjoint
+// of the local backward state that enters the tile from the left (BwdParams::gck).
+bool needs_gamma_checkpoints(const FwdParams& f)
+{
+    return f.seqlen > kTileTokens && kTileTokens % f.window != 0;
+}
+
 struct BwdLayout {
     Shape shape;            // segments in forward tiles (32 tokens)
     size_t ntiles16;        // backward tiles (16 tokens) per row
-    size_t ckpt, cum, carry, dsum, psi, acc, part;   // float offsets into the workspace
+    size_t ckpt, cum, gck, carry, dsum, psi, part;   // float offsets into the workspace
     size_t total;           // floats
 };
 
-BwdLayout bwd_layout(const FwdParams& f, int local_window)
+BwdLayout bwd_layout(const FwdParams& f)
 {
     BwdLayout l;
     l.shape = pick_shape(f);
+    const bool gamma = needs_gamma_checkpoints(f);
+    if (gamma && l.shape.nseg > 1) {
+        // segments must start at window starts: whole windows per segment
+        long g = f.window, r = kFwdTileTokens;
+        while (r) { const long t = g % r; g = r; r = t; }          // gcd(window, 32)
+        const long unit = f.window / g;                            // forward tiles per window period
+        const long ntiles = (f.seqlen + kFwdTileTokens - 1) / kFwdTileTokens;
+        long st = ((l.shape.seg_tiles + unit - 1) / unit) * unit;
+        if (st >= ntiles) st = ntiles;
+        l.shape.seg_tiles = (int)st;
+        l.shape.nseg = (int)((ntiles + st - 1) / st);
+    }
     const size_t rows = (size_t)f.batch * f.dim, N = f.dstate;
     l.ntiles16 = (f.seqlen + kTileTokens - 1) / kTileTokens;
     size_t o = 0;
     l.ckpt = o; o += l.ntiles16 * rows * N;
     l.cum = o;  o += l.ntiles16 * rows;
+    l.gck = o;  if (gamma) o += l.ntiles16 * rows * N;
     const size_t ns = l.shape.nseg > 1 ? l.shape.nseg : 0;
     l.carry = o; o += ns * rows * N;
     l.dsum = o;  o += ns * rows;
     l.psi = o;   o += ns * rows * N;
-    l.acc = o;
-    if (f.dtype != 0) o += 2 * (size_t)f.batch * N * f.seqlen;     // fp32 dBm, dCm
-    l.part = o;
-    // fp32 dx, ddelta, dz of the fused kernel, for the kernel of the local backward part
-    if (f.dtype != 0 && local_window > 0) o += 3 * rows * (size_t)f.seqlen;
+    l.part = o;                                // per block of 64 channels: fp32 dBm, dCm
+    o += 2 * (size_t)((f.dim + 63) / 64) * f.batch * N * f.seqlen;
     l.total = o;
     return l;
 }
 
 }  // namespace
 
-size_t bwd_workspace_bytes(const FwdParams& f, int local_window)
+size_t bwd_workspace_bytes(const FwdParams& f)
 {
     if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return 0;
-    return bwd_layout(f, local_window).total * sizeof(float);
+    return bwd_layout(f).total * sizeof(float);
 }
 
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
-                      const float* saved, const float* dhT, int local_window, hipStream_t stream)
+                      const float* saved, const float* dhT, hipStream_t stream)
 {
     if (f.batch == 0 || f.dim == 0 || f.seqlen == 0) return hipSuccess;
     if (!workspace) return hipErrorInvalidValue;
-    const BwdLayout l = bwd_layout(f, local_window);
+    const BwdLayout l = bwd_layout(f);
     const Shape& s = l.shape;
+    const bool gamma = needs_gamma_checkpoints(f);
     float* ws = static_cast<float*>(workspace);
     const long bnl = (long)f.batch * f.dstate * f.seqlen;
-    const size_t bdl = (size_t)f.batch * f.dim * f.seqlen;
-    const bool parts = f.dtype != 0 && local_window > 0;
-    p.part_dx = parts ? ws + l.part : nullptr;
-    p.part_ddelta = parts ? ws + l.part + bdl : nullptr;
-    p.part_dz = parts ? ws + l.part + 2 * bdl : nullptr;
-    p.dBacc = f.dtype == 0 ? static_cast<float*>(dBm) : ws + l.acc;
-    p.dCacc = f.dtype == 0 ? static_cast<float*>(dCm) : ws + l.acc + bnl;
+    p.dBpart = ws + l.part;
     p.ckpt = ws + l.ckpt;
     p.cum = ws + l.cum;
+    p.gck = gamma ? ws + l.gck : nullptr;
     p.nseg = s.nseg;
     p.seg_tiles = s.seg_tiles * (kFwdTileTokens / kTileTokens);
     // uncut rows: the entering state and the gradient arriving at the leaving state
@@ -214,38 +227,18 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
     p.psi_in = s.nseg > 1 ? ws + l.psi : dhT;
 
     hipError_t e;
-    const ZeroMany z{{p.dBacc, p.dCacc, p.dA, p.dDskip, p.dbias},
-                     {bnl, bnl, (long)f.dim * f.dstate, f.dim, f.dim}};
+    const ZeroMany z{{p.dA, p.dDskip, p.dbias, nullptr, nullptr},
+                     {(long)f.dim * f.dstate, f.dim, f.dim, 0, 0}};
     if ((e = launch_zero_many(z, stream)) != hipSuccess) return e;
 
-    // what follows the fused kernel: the local backward part of a window length
-    // without a fused kernel (independent tiles of whole windows, cut into enough
-    // segments to fill the chip), then the conversion of the fp32 accumulators
+    // after the backward kernel: dBm, dCm from the per-block partial sums
     auto finish = [&]() -> hipError_t {
-        hipError_t r = hipSuccess;
-        if (local_window > 0) {
-            BwdParams q = p;
-            q.window = local_window;
-            const long tl = (long)(kTileTokens / local_window) * local_window;
-            const long ntiles = (f.seqlen + tl - 1) / tl;
-            const long nrb = (long)((f.dim + 63) / 64) * f.batch;
-            long want = nrb < 512 ? (512 + nrb - 1) / nrb : 1;       // two blocks per CU are resident
-            if (f.force_nseg >= 1) want = f.force_nseg;
-            long st = (ntiles + want - 1) / want;
-            if (st < 1) st = 1;
-            q.seg_tiles = (int)st;
-            q.nseg = (int)((ntiles + st - 1) / st);
-            r = f.dtype == 0 ? launch_bwd_local_f32(q, stream) : launch_bwd_local_bf16(q, stream);
-            if (r != hipSuccess) return r;
-        }
-        if (f.dtype != 0) {
-            if ((r = launch_convert_bf16(p.dBacc, dBm, bnl, stream)) != hipSuccess) return r;
-            if ((r = launch_convert_bf16(p.dCacc, dCm, bnl, stream)) != hipSuccess) return r;
-        }
-        return r;
+        const int nbx = (f.dim + 63) / 64;
+        return f.dtype == 0 ? launch_reduce_f32(p.dBpart, dBm, dCm, bnl, nbx, stream)
+                            : launch_reduce_bf16(p.dBpart, dBm, dCm, bnl, nbx, stream);
     };
 
-    if (saved && s.nseg == 1) {
+    if (saved && s.nseg == 1 && !gamma) {
         // the forward call left the checkpoints (entering state included): no summary pass
         p.ckpt = saved;
         p.cum = nullptr;
@@ -256,13 +249,15 @@ hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, voi
 
     // summary pass (the forward kernel in summary mode): checkpoints of f for every
     // 16-token tile and, when the rows are cut, the per-segment summaries of the
-    // forward and of the right-to-left recurrence
+    // forward and of the right-to-left recurrence; for windows that straddle tile
+    // starts also the checkpoints of the adjoint of the local backward state
     FwdParams q = f;
     q.nseg = s.nseg;
     q.seg_tiles = s.seg_tiles;
     q.summary_only = 1;
     q.ckpt = ws + l.ckpt;
     q.cum = ws + l.cum;
+    q.gck = gamma ? ws + l.gck : nullptr;
     q.carry = s.nseg > 1 ? ws + l.carry : nullptr;
     q.dsum = s.nseg > 1 ? ws + l.dsum : nullptr;
     q.psi = s.nseg > 1 ? ws + l.psi : nullptr;

@@ -35,7 +35,7 @@ struct FwdParams {
     float* carry;         // nullable when nseg == 1
     float* dsum;
     // summary pass only: per-tile checkpoints for the backward pass (nullable):
-    // ckpt (ntiles, B*D, N) state at the start of each tile, cum (ntiles, B*D)
+    // ckpt (ntiles, N, B*D) state at the start of each tile, cum (ntiles, B*D)
     // time-step sum up to there, both counted from the start of the segment
     float* ckpt;
     float* cum;
@@ -43,6 +43,9 @@ struct FwdParams {
     // psi (nseg, B*D, N) out: the segment's summary of the right-to-left recurrence
     const void* dout;
     float* psi;
+    // summary pass for window lengths that 16 is not a multiple of (nullable):
+    // gck (ntiles16, N, B*D), see lbscan_fwd_rowlane.inc MODE 2
+    float* gck;
     // forward state entering the row (nullable: zeros) and leaving it (nullable), (B*D, N)
     const float* h0;
     float* hT;
@@ -72,26 +75,21 @@ struct BwdParams {
     void* dx;
     void* ddelta;
     void* dz;             // nullable iff z is
-    float* dBacc;         // (B,N,L) fp32, zeroed: dBm accumulates here
-    float* dCacc;
+    float* dBpart;        // fp32 partial sums [dBm | dCm][block of 64 channels][B][N][L]: every
+                          // block of the backward kernel writes its own share
     float* dA;            // (D,N) zeroed
     float* dDskip;        // (D) zeroed, nullable
     float* dbias;         // (D) zeroed, nullable
-    const float* ckpt;    // (ntiles, B*D, N): f at the first step of every tile, counted
+    const float* ckpt;    // (ntiles, N, B*D): f at the first step of every tile, counted
                           // from the start of the tile's segment
     // rows cut into nseg segments of seg_tiles backward tiles (16 tokens each):
     int nseg, seg_tiles;
     const float* cum;     // (ntiles, B*D): time-step sum from the segment start to the tile
     const float* carry;   // (nseg, B*D, N): forward state entering each segment (null: zeros)
     const float* psi_in;  // (nseg, B*D, N): psi entering each segment from the right
+    const float* gck;     // (ntiles, N, B*D), nullable: abar_{t-1} gamma_{t-1} entering each tile
+                          // (windows that straddle tile starts)
     float* dh0;           // (B*D, N), nullable: psi leaving the row on the left
-    // (B,D,L) fp32, nullable.  When set, the fused kernel leaves dx, ddelta, dz here
-    // instead of in dx, ddelta, dz, and the kernel of the local backward part
-    // reads them from here, adds its share and writes dx, ddelta, dz: with 2-byte
-    // storage the two shares must meet in fp32 (they may cancel).
-    float* part_dx;
-    float* part_ddelta;
-    float* part_dz;
 };
 
 // Arguments of the pre-scan convolution kernels (lbscan_conv.hip).
@@ -138,13 +136,10 @@ size_t saved_state_bytes(const FwdParams& p);
 // Backward kernels (lbscan_bwd_rowlane.inc), one translation unit per storage type.
 hipError_t launch_bwd_rowlane_f32(const BwdParams& p, hipStream_t stream);
 hipError_t launch_bwd_rowlane_bf16(const BwdParams& p, hipStream_t stream);
-// Backward kernel of the local backward part alone (lbscan_bwd_local.inc): adds its
-// gradients to what the fused kernel left for window 1.  p.window <= kTileTokens;
-// p.seg_tiles counts tiles of (kTileTokens / window) * window tokens.
-hipError_t launch_bwd_local_f32(const BwdParams& p, hipStream_t stream);
-hipError_t launch_bwd_local_bf16(const BwdParams& p, hipStream_t stream);
-hipError_t launch_convert_f32(const float* src, void* dst, long n, hipStream_t stream);
-hipError_t launch_convert_bf16(const float* src, void* dst, long n, hipStream_t stream);
+// dBm, dCm (storage type) = the partial sums of BwdParams::dBpart added over the nbx
+// blocks of 64 channels; bnl = B * N * L.
+hipError_t launch_reduce_f32(const float* part, void* dB, void* dC, long bnl, int nbx, hipStream_t stream);
+hipError_t launch_reduce_bf16(const float* part, void* dB, void* dC, long bnl, int nbx, hipStream_t stream);
 // Sets n floats to zero with a kernel (a memset node must not be recorded into
 // a captured graph).
 hipError_t launch_zero(float* dst, long n, hipStream_t stream);
@@ -155,24 +150,18 @@ hipError_t launch_zero_many(ZeroMany z, hipStream_t stream);
 
 // Whole backward pass: zero the accumulators, checkpoint pass, backward kernel,
 // conversion of dBm / dCm when the storage type is not fp32.  dBm / dCm are the
-// caller's outputs; workspace must hold bwd_workspace_bytes(f) bytes.
+// caller's outputs; workspace must hold bwd_workspace_bytes(f) bytes.  f.window is
+// any window length >= 1 (1, 2, 4 run with a compiled window structure, all others
+// with run-time window masks).
 // saved (nullable): checkpoints left by launch_fwd on the same inputs.
 // dhT (nullable): gradient arriving at the state that leaves the row.
-// local_window > 0: f.window is 1 and the gradients of the local backward part for
-// that window length (<= kTileTokens, no fused kernel) are added by a second kernel.
 hipError_t launch_bwd(const FwdParams& f, BwdParams p, void* dBm, void* dCm, void* workspace,
-                      const float* saved, const float* dhT, int local_window, hipStream_t stream);
-size_t bwd_workspace_bytes(const FwdParams& f, int local_window = 0);
+                      const float* saved, const float* dhT, hipStream_t stream);
+size_t bwd_workspace_bytes(const FwdParams& f);
 
 // Depthwise causal convolution + SiLU along the sequence and its gradient.
 hipError_t launch_conv1d_fwd(const ConvParams& p, hipStream_t stream);
 hipError_t launch_conv1d_bwd(const ConvParams& p, hipStream_t stream);
-
-// Issue-rate probes (lbscan_probe.hip): `blocks` blocks of 256 lanes, every lane
-// executing probe_ops_per_lane(iters) instructions of kind which (0 fp32 fma, 1
-// exp2, 2 rcp); out holds blocks * 256 floats.
-hipError_t launch_probe(int which, int blocks, int iters, float* out, hipStream_t stream);
-long probe_ops_per_lane(int iters);
 
 // Chains the per-segment summaries into the states entering each segment
 // (lbscan_carry.hip): carry[s] <- exclusive scan over s of (exp(A*dsum), carry),

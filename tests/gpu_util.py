@@ -25,6 +25,13 @@ def assert_close(got, ref, dtype="fp32", what="out"):
     assert np.all(np.isfinite(got)), f"{what}: non-finite values"
     assert err <= tol, f"{what}: scale-aware max rel err {err:.3e} > {tol}"
     assert merr <= mtol, f"{what}: mean abs err / rms {merr:.3e} > {mtol}"
+    if np.asarray(ref).size >= 1 << 20:
+        # full-size cases: the figure with the floor at 1e-3 rms (what any fp32
+        # evaluation scores there, the correctly rounded sequential one included) is
+        # reported next to the tested one (floor 0.1 rms); run pytest with -s to see it
+        strict = error_metric(got, ref, floor_frac=1e-3)
+        print(f"[parity] {what}: max rel err {err:.3e} (floor 0.1 rms, tested <= {tol}); "
+              f"{strict:.3e} (floor 1e-3 rms, reported); mean abs err / rms {merr:.3e}")
     return err
 
 

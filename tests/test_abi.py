@@ -52,7 +52,7 @@ def test_default_window_rule(lib):
 
 
 def test_validation_without_gpu(lib):
-    from paper_2506_15976_amd.binding import LbscanArgs, EINVAL, EUNSUPPORTED, OK
+    from paper_2506_15976_amd.binding import LbscanArgs, EINVAL, EUNSUPPORTED, EWORKSPACE, OK
     a = LbscanArgs()
     a.batch, a.dim, a.dstate, a.seqlen, a.window = 1, 4, 16, 8, 0
     assert lib.lbscan_fwd(ctypes.byref(a), None) == EINVAL          # window < 1
@@ -70,10 +70,18 @@ def test_validation_without_gpu(lib):
     a.seqlen = 64
     a.window = 3
     a.x = a.delta = a.y = a.A = a.Bm = a.Cm = 256                   # never dereferenced on the host
-    # the backward pass of window lengths without a fused kernel stops at 16 tokens
+    # every window length has a backward pass: with no workspace given the call stops
+    # at the workspace check, not at the window
     fake = ctypes.c_void_p(256)
-    a.window = 17
+    for window in (3, 17, 100):
+        a.window = window
+        assert lib.lbscan_bwd(ctypes.byref(a), *([fake] * 9), None) == EWORKSPACE
+    # a state size of zero with steps to take has no kernel (and must not reach one)
+    a.dstate, a.window = 0, 4
+    assert lib.lbscan_fwd(ctypes.byref(a), None) == EUNSUPPORTED
     assert lib.lbscan_bwd(ctypes.byref(a), *([fake] * 9), None) == EUNSUPPORTED
+    assert lib.lbscan_bidir_fwd(ctypes.byref(a), ctypes.byref(a), None) == EUNSUPPORTED
+    a.dstate = 16
     a.x = 257
     a.window = 4
     assert lib.lbscan_fwd(ctypes.byref(a), None) == EINVAL          # misaligned pointer
@@ -99,25 +107,35 @@ def test_workspace_sizes_follow_the_launch_plan(lib):
     a = LbscanArgs()
     a.batch, a.dim, a.dstate, a.seqlen, a.window = B, D, N, L, 4
     ws = lambda which: lib.lbscan_workspace_bytes(ctypes.byref(a), which)
-    rows, tiles16 = B * D, (L + 15) // 16
+    rows, tiles16, nbx = B * D, (L + 15) // 16, (D + 63) // 64
+    part = 2 * nbx * B * N * L          # fp32 dBm, dCm per block of 64 channels
     try:
         assert lib.lbscan_set_option(b"segments", 1) == 0
         assert ws(WS_FWD) == 0
         assert ws(WS_SAVED) == tiles16 * rows * N * 4
-        assert ws(WS_BWD) == (tiles16 * rows * N + tiles16 * rows) * 4          # checkpoints + dt sums
-        a.dtype = 1                                                            # bf16: + fp32 dBm, dCm
-        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + 2 * B * N * L) * 4
-        a.window = 3                                                           # no fused kernel
+        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + part) * 4              # checkpoints + dt sums + partials
+        a.dtype = 1                                                            # bf16: the same (fp32 scratch)
+        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + part) * 4
+        a.window = 8                                                           # run-time window masks, tiles aligned
+        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + part) * 4
+        a.window = 3                                                           # no fused forward kernel
         assert ws(WS_FWD) == rows * L * 4                                      # fp32 first-pass result
         assert ws(WS_SAVED) == 0
-        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + 2 * B * N * L + 3 * rows * L) * 4
+        # windows straddle tile starts: checkpoints of the local adjoint as well
+        assert ws(WS_BWD) == (tiles16 * rows * (2 * N + 1) + part) * 4
         a.window = 17
-        assert ws(WS_BWD) == 0                                                 # unsupported
+        assert ws(WS_BWD) == (tiles16 * rows * (2 * N + 1) + part) * 4
+        a.window = 1000                                                        # one window: as window = L
+        assert ws(WS_BWD) == (tiles16 * rows * (2 * N + 1) + part) * 4
         a.dtype, a.window = 0, 4
         assert lib.lbscan_set_option(b"segments", 3) == 0                      # 7 tiles of 32 -> 3 + 3 + 1
         assert ws(WS_FWD) == 3 * rows * (N + 1) * 4
         assert ws(WS_SAVED) == 0
-        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + 3 * rows * (2 * N + 1)) * 4
+        assert ws(WS_BWD) == (tiles16 * rows * (N + 1) + 3 * rows * (2 * N + 1) + part) * 4
+        a.window = 3                          # segments of whole windows: 3 tiles of 32 hold 32 windows
+        assert ws(WS_BWD) == (tiles16 * rows * (2 * N + 1) + 3 * rows * (2 * N + 1) + part) * 4
+        a.window = 5                          # 5 tiles of 32 per segment: 7 tiles -> 2 segments
+        assert ws(WS_BWD) == (tiles16 * rows * (2 * N + 1) + 2 * rows * (2 * N + 1) + part) * 4
     finally:
         assert lib.lbscan_set_option(b"segments", 0) == 0
     assert lib.lbscan_set_option(b"segments", -1) != 0

@@ -187,8 +187,9 @@ def test_gradients_with_extreme_time_steps_and_decay_rates(lb, oracle):
 ])
 @pytest.mark.parametrize("reverse", [False, True])
 def test_gradients_any_window_up_to_a_tile(lb, oracle, shape, window, reverse):
-    """Window lengths without a fused kernel: gradients of the plain scan from the
-    fused kernel with window 1 plus those of the local backward part."""
+    """Window lengths that 16 is not a multiple of: the backward kernel runs with
+    run-time window masks and takes the adjoint of the local backward state that
+    enters each 16-token tile from the summary pass."""
     from paper_2506_15976_amd.inputs import make_inputs
     B, D, N, L = shape
     s = make_inputs(B, D, N, L, seed=9400 + L + window, with_dout=True, random_A=True)
@@ -206,6 +207,36 @@ def test_gradients_any_window_long_rows_in_segments(lb, oracle, nseg, dtype):
         _run_bwd(lb, oracle, s, window=10, dtype=dtype, reverse=True)
     finally:
         lb.lbscan_set_option("segments", 0)
+
+
+@pytest.mark.parametrize("shape,window", [
+    ((2, 70, 16, 137), 17), ((1, 130, 16, 197), 24), ((1, 64, 16, 200), 32), ((2, 33, 8, 333), 100),
+    ((1, 64, 16, 197), 196), ((1, 64, 16, 100), 99), ((1, 64, 16, 64), 48),
+])
+@pytest.mark.parametrize("reverse", [False, True])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_gradients_windows_longer_than_a_tile(lb, oracle, shape, window, reverse, dtype):
+    """Sec. 3.2 leaves the window length free: windows longer than the 16-token tile
+    (M < L), whose adjoint of the local backward state crosses tile boundaries."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    B, D, N, L = shape
+    s = make_inputs(B, D, N, L, seed=9500 + L + window, with_dout=True, random_A=True, dtype=dtype)
+    _run_bwd(lb, oracle, s, window=window, reverse=reverse, dtype=dtype)
+
+
+@pytest.mark.parametrize("nseg", [2, 5])
+def test_gradients_long_windows_long_rows_in_segments(lb, oracle, nseg):
+    """Segments are whole windows when windows straddle tile starts."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(1, 70, 16, 2000, seed=9520 + nseg, with_dout=True)
+    lb.lbscan_set_option("segments", nseg)
+    try:
+        _run_bwd(lb, oracle, s, window=24)
+        _run_bwd(lb, oracle, s, window=100, reverse=True)
+        _run_bwd(lb, oracle, s, window=7)
+    finally:
+        lb.lbscan_set_option("segments", 0)
+    _run_bwd(lb, oracle, s, window=40)          # default segmentation of a long row
 
 
 def test_gradients_any_window_without_optionals_and_default_segments(lb, oracle):

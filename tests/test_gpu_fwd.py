@@ -125,6 +125,28 @@ def test_optional_arguments_absent(lb, oracle):
     _run_fwd(lb, oracle, s2, window=4, softplus=False)
 
 
+def test_call_on_a_side_stream(lb, oracle):
+    """The binding's scratch and outputs are tied to the stream the kernels run on
+    (default priority), not only to the current one."""
+    import torch
+    from gpu_util import assert_close, fwd_inputs, to_device, to_numpy
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(1, 64, 16, 3000, seed=55, with_dout=True)      # long rows: scratch in use
+    dev = to_device(s, "fp32")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    out = lb.lbscan_fwd(**fwd_inputs(dev), window=4, stream=side)
+    g = lb.lbscan_bwd(**fwd_inputs(dev), dout=dev["dout"], window=4, stream=side)
+    junk = [torch.full((1 << 20,), float("nan"), device="cuda:0") for _ in range(8)]   # current stream
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert_close(to_numpy(out), oracle.fwd(**fwd_inputs(s), window=4), "fp32")
+    ref = oracle.bwd(**fwd_inputs(s), dout=s["dout"], window=4)
+    for k in ("dx", "dBm", "dA"):
+        assert_close(to_numpy(g[k]), ref[k], "fp32", k)
+    del junk
+
+
 def test_window_covering_short_row(lb, oracle):
     """M >= L with L <= 16 is one window over the whole row."""
     from paper_2506_15976_amd.inputs import make_inputs
@@ -133,15 +155,21 @@ def test_window_covering_short_row(lb, oracle):
     _run_fwd(lb, oracle, s, window=1000)
 
 
-def test_backward_of_a_long_window_without_fused_kernel_is_an_error(lb):
-    """The backward pass of window lengths without a fused kernel covers windows of
-    up to 16 tokens."""
-    from gpu_util import fwd_inputs, to_device
+def test_any_window_bf16_rows_of_even_length_with_odd_windows(lb, oracle):
+    """2-byte storage, even row length, odd window length: the second pass walks
+    segments of odd length, whose mirrored quads would start at odd elements; they
+    must take the element-wise path (default segmentation and forced cuts)."""
     from paper_2506_15976_amd.inputs import make_inputs
-    dev = to_device(make_inputs(1, 64, 16, 64, seed=6, with_dout=True), "fp32")
-    with pytest.raises(lb.LbscanError) as ei:
-        lb.lbscan_bwd(**fwd_inputs(dev), dout=dev["dout"], window=17)
-    assert ei.value.code == -2
+    s = make_inputs(1, 70, 16, 1000, seed=77, dtype="bf16")
+    for window in (5, 3, 13):
+        _run_fwd(lb, oracle, s, window=window, dtype="bf16")
+        _run_fwd(lb, oracle, s, window=window, dtype="bf16", reverse=True)
+    lb.lbscan_set_option("segments", 7)
+    try:
+        _run_fwd(lb, oracle, s, window=5, dtype="bf16")
+        _run_fwd(lb, oracle, s, window=5, dtype="bf16", reverse=True)
+    finally:
+        lb.lbscan_set_option("segments", 0)
 
 
 @pytest.mark.parametrize("shape,window", [
