@@ -111,6 +111,21 @@ typedef struct lbscan_args {
  * the global forward scan of Eq. 1-3; gate and skip of Algorithm 1 fused in). */
 int lbscan_fwd(const lbscan_args *args, void *hip_stream);
 
+/* lbscan_fwd for callers that cannot allocate or hand over scratch: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  The same
+ * computation and the same kernels, with the scratch of long rows (carried states of
+ * the row segments) in a fixed device array of LBSCAN_STATIC_SCRATCH_BYTES that the
+ * library holds on every GPU it runs on until the process ends; args->workspace is
+ * ignored.  Nothing is allocated or freed, here or in the runtime (the array's
+ * address is looked up once per device, on the first call there).  Sizes that need
+ * more scratch than the array holds (lbscan_workspace_bytes(args, LBSCAN_WS_FWD))
+ * return LBSCAN_EWORKSPACE, with the two sizes in lbscan_last_error().  Every call on
+ * a GPU shares that GPU's array: calls that overlap on one GPU (different streams)
+ * race; calls on one stream are ordered.  Nothing in the array needs clearing
+ * between calls (each call writes what it reads). */
+#define LBSCAN_STATIC_SCRATCH_BYTES (8u << 20)
+int lbscan_fwd_static(const lbscan_args *args, void *hip_stream);
+
 /* Gradients of lbscan_fwd with respect to every input (the paper reports only
  * training throughput, Appendix B; the formulas are the reverse-mode derivative
  * of the forward definition above).  fwd_args names the forward inputs

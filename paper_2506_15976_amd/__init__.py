@@ -6,6 +6,6 @@ binding with the same entry-point names.
 """
 from .binding import (  # noqa: F401
     LbscanArgs, LbscanConvArgs, LbscanError, lbscan_bidir_fwd, lbscan_bwd, lbscan_conv1d_bwd, lbscan_conv1d_fwd,
-    lbscan_default_window, lbscan_fwd, lbscan_saved_state, lbscan_set_option, lbscan_version,
+    lbscan_default_window, lbscan_fwd, lbscan_fwd_static, lbscan_saved_state, lbscan_set_option, lbscan_version,
     lbscan_workspace_bytes, load, make_args,
 )

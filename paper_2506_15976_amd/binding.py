@@ -21,6 +21,7 @@ EXPORTS = (
     "lbscan_fwd", "lbscan_bwd", "lbscan_bidir_fwd", "lbscan_workspace_bytes",
     "lbscan_default_window", "lbscan_strerror", "lbscan_last_error", "lbscan_version",
     "lbscan_set_option", "lbscan_bwd_state", "lbscan_conv1d_fwd", "lbscan_conv1d_bwd",
+    "lbscan_fwd_static",
 )
 
 
@@ -75,6 +76,8 @@ def load():
     vp = ctypes.c_void_p
     lib.lbscan_fwd.restype = ctypes.c_int
     lib.lbscan_fwd.argtypes = [ap, vp]
+    lib.lbscan_fwd_static.restype = ctypes.c_int
+    lib.lbscan_fwd_static.argtypes = [ap, vp]
     lib.lbscan_bidir_fwd.restype = ctypes.c_int
     lib.lbscan_bidir_fwd.argtypes = [ap, ap, vp]
     lib.lbscan_bwd.restype = ctypes.c_int
@@ -104,7 +107,7 @@ def _check(rc: int, name: str):
     if rc != OK:
         lib = load()
         msg = lib.lbscan_strerror(rc).decode()
-        if rc == EHIP:
+        if rc == EHIP or (rc == EWORKSPACE and name.endswith("_static")):
             msg += ": " + lib.lbscan_last_error().decode()
         raise LbscanError(rc, f"{name} failed ({rc}): {msg}")
 
@@ -243,6 +246,19 @@ def lbscan_fwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, wind
     _check(load().lbscan_fwd(ctypes.byref(a), _stream(stream)), "lbscan_fwd")
     del ws
     return (y, hT) if return_state else y
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def lbscan_fwd_static(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, out, window,
+                      delta_softplus=True, reverse=False, stream=None, h0=None, hT=None):
+    """lbscan_fwd without any allocation: the caller passes every output (out, and hT
+    if wanted); scratch is the library's fixed device array (see include/lbscan.h)."""
+    a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
+                  delta_softplus=delta_softplus, reverse=reverse, y=out, h0=h0, hT=hT)
+    _check(load().lbscan_fwd_static(ctypes.byref(a), _stream(stream)), "lbscan_fwd_static")
+    return out
 
 
 def lbscan_bidir_fwd(set_f: dict, set_b: dict, *, out=None, stream=None):

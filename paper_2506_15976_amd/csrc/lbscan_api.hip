@@ -5,6 +5,7 @@
 #include "lbscan_internal.h"
 
 #include <atomic>
+#include <mutex>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
@@ -17,6 +18,16 @@ int hip_fail(hipError_t e, const char* where)
 {
     snprintf(g_last_error, sizeof(g_last_error), "%s: %s", where, hipGetErrorString(e));
     return LBSCAN_EHIP;
+}
+
+// Scratch missing or too small; for the fixed array the text says what was asked for.
+int scratch_too_small(size_t need, size_t have, bool fixed)
+{
+    if (fixed)
+        snprintf(g_last_error, sizeof(g_last_error),
+                 "lbscan_fwd_static: these sizes need %zu bytes of scratch, the fixed array holds %zu",
+                 need, have);
+    return LBSCAN_EWORKSPACE;
 }
 
 // Launch-shape overrides set through lbscan_set_option (tuning and tests).
@@ -114,11 +125,61 @@ lbscan::ConvParams to_conv_params(const lbscan_conv_args* a)
     return p;
 }
 
+// ---- scratch of lbscan_fwd_static ----------------------------------------------
+// A fixed device array that every GPU the library runs on holds until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address is looked up once per device and that pointer, never the name, is
+// what the kernels get.
+static __device__ __align__(256) unsigned char g_static_scratch[LBSCAN_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices] = {};
+
+// Device address of the scratch array on the current device (nullptr and *err set on
+// failure).  The first call on a device asks the runtime; no allocation either way.
+void* static_scratch(hipError_t* err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* ptr = nullptr;
+        *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch));
+        if (*err != hipSuccess) return nullptr;
+        g_static_ptr[dev] = ptr;
+    }
+    return g_static_ptr[dev];
+}
+
+// lbscan_fwd with the scratch given explicitly (bytes available at `scratch`).
+int fwd_with_scratch(const lbscan_args* args, void* scratch, size_t scratch_bytes, bool fixed, void* hip_stream);
+
 }  // namespace
 
 extern "C" {
 
 int lbscan_fwd(const lbscan_args* args, void* hip_stream)
+{
+    return fwd_with_scratch(args, args ? args->workspace : nullptr, args ? args->workspace_bytes : 0, false,
+                            hip_stream);
+}
+
+int lbscan_fwd_static(const lbscan_args* args, void* hip_stream)
+{
+    hipError_t e = hipSuccess;
+    void* ptr = static_scratch(&e);
+    if (!ptr) return hip_fail(e, "lbscan_fwd_static: address of the scratch array");
+    return fwd_with_scratch(args, ptr, LBSCAN_STATIC_SCRATCH_BYTES, true, hip_stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int fwd_with_scratch(const lbscan_args* args, void* scratch, size_t scratch_bytes, bool fixed, void* hip_stream)
 {
     bool empty;
     int rc = check_args(args, true, &empty);
@@ -136,24 +197,28 @@ int lbscan_fwd(const lbscan_args* args, void* hip_stream)
         // no compiled kernel for this window length: the two-launch path
         lbscan::FwdParams p = to_params(args, args->window < args->seqlen ? args->window : args->seqlen);
         const size_t need = lbscan::fwd_generic_workspace_bytes(p);
-        if (need && (!args->workspace || args->workspace_bytes < need || !aligned4(args->workspace)))
-            return LBSCAN_EWORKSPACE;
-        hipError_t e = lbscan::launch_fwd_generic(p, args->workspace, static_cast<hipStream_t>(hip_stream));
+        if (need && (!scratch || scratch_bytes < need || !aligned4(scratch)))
+            return scratch_too_small(need, scratch_bytes, fixed);
+        hipError_t e = lbscan::launch_fwd_generic(p, scratch, static_cast<hipStream_t>(hip_stream));
         return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_fwd");
     }
     lbscan::FwdParams p = to_params(args, M);
     const size_t need = lbscan::fwd_workspace_bytes(p);
-    if (need && (!args->workspace || args->workspace_bytes < need || !aligned4(args->workspace)))
-        return LBSCAN_EWORKSPACE;
+    if (need && (!scratch || scratch_bytes < need || !aligned4(scratch)))
+        return scratch_too_small(need, scratch_bytes, fixed);
     float* saved = nullptr;
     if (args->saved_state) {
         const size_t sneed = lbscan::saved_state_bytes(p);
         if (sneed && (args->saved_state_bytes < sneed || !aligned4(args->saved_state))) return LBSCAN_EWORKSPACE;
         if (sneed) saved = static_cast<float*>(args->saved_state);
     }
-    hipError_t e = lbscan::launch_fwd(p, args->workspace, saved, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = lbscan::launch_fwd(p, scratch, saved, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? LBSCAN_OK : hip_fail(e, "lbscan_fwd");
 }
+
+}  // namespace
+
+extern "C" {
 
 int lbscan_bidir_fwd(const lbscan_args* fs, const lbscan_args* bs, void* hip_stream)
 {
