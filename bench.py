@@ -3,13 +3,16 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
-A step is one lbscan_fwd call over one batch of synthetic input (the
-Vim-tiny-shaped workload by default).  Inputs are resident in HBM before the
-timed region; launches rotate over several independent input sets so that the
-256 MB Infinity Cache cannot serve them.  One JSON line is printed:
-tokens/s of the locally bi-directional scan, the HBM roofline of its kernel,
+A step is one lbscan_fwd call over one batch of synthetic input: the
+Vim-small-shaped workload by default (the shape the target is quoted on).
+Inputs are resident in HBM before the timed region; launches rotate over several
+independent input sets so that the 256 MB Infinity Cache cannot serve them.  One
+JSON line is printed: tokens/s of the locally bi-directional scan, the HBM
+roofline of its kernel, the fp32 issue bound at the algorithmic operation count,
 the speed-up over the two-pass global bi-directional scan on the same inputs,
-and the fp64 CPU oracle timed on the host cores as a reported baseline.
+the fp64 CPU oracle timed on the host cores as a reported baseline, and under
+"workloads" the same figures (forward, two-pass comparison, backward) for every
+named workload.
 """
 import argparse
 import ctypes
@@ -25,13 +28,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # Plain (unpacked) fp32 VALU issue: 256 CUs x 64 lanes x 2.4 GHz; packed FP32 is off by
 # build rule, so the 157.3 TFLOP/s figure (packed FMA) does not apply.  v_exp_f32 issues
-# at half rate on this chip (measured), i.e. it takes two issue slots.
+# at half rate on this chip (measured: 19.2 T/s against 38.6 T/s for fma, and the two do
+# not overlap), i.e. it takes two issue slots.
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
-# Issue slots per state update of rowlane_fwd_kernel, from SQ_INSTS_VALU and
-# SQ_INSTS_VALU_TRANS_F32 in profiles/lbscan_counters_vim_small.md (10.4 VALU instructions
-# incl. 1.3 transcendental, which take two slots each).
-FWD_SLOTS_PER_STATE_UPDATE = 11.7
-FWD_VALU_PER_SU, FWD_TRANS_PER_SU = 9.1, 1.3
+# Issue slots per state update of the forward kernel as measured (SQ_INSTS_VALU +
+# SQ_INSTS_VALU_TRANS_F32, profiles/lbscan_counters_vim_small.md): secondary figure.
+FWD_SLOTS_MEASURED = 11.05
 FWD_KEYS = ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")
 
 # L2-to-fabric bytes per lbscan_fwd call from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
@@ -47,19 +49,26 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def alu_bound(su_per_s, rates):
-    """fp32 VALU issue bound of the forward kernel at its present instruction count:
-    FWD_VALU_PER_SU plain instructions and FWD_TRANS_PER_SU transcendental ones per
-    state update, priced at the nominal issue peak (transcendentals at half rate) or,
-    with measured rates, at what the probe kernels reached on this machine."""
-    if rates:
-        t = FWD_VALU_PER_SU / rates["fma"] + FWD_TRANS_PER_SU / rates["exp2"]
-        peak, how = 1.0 / t, "measured issue rates"
-    else:
-        peak, how = VALU_PEAK_LANE_OPS / FWD_SLOTS_PER_STATE_UPDATE, "nominal issue peak"
-    return {"unit": "state updates/s", "achieved": su_per_s, "peak": peak, "frac": su_per_s / peak,
-            "rates_lane_ops_per_s": rates,
-            "note": f"fp32 VALU issue bound of the forward kernel at its present instruction count, {how}"}
+def algorithmic_slots(window):
+    """fp32 issue slots one state update needs in the leanest sequential form of the
+    method (Eq. 1, 3, 7, 8): dt*A (1), exp (2: half rate), u = (dt x) B (1), f = fma (1),
+    y += C h (1), and per window of M steps M-2 fmas for the local backward state and M-1
+    for h = f + abar S: 6 + (2M-3)/M for M >= 2, 6 for M = 1 (7.25 at M = 4)."""
+    m = max(int(window), 1)
+    return 6.0 + (max(2 * m - 3, 0) / m if m >= 2 else 0.0)
+
+
+def alu_bound(su_per_s, window):
+    slots = algorithmic_slots(window)
+    peak = VALU_PEAK_LANE_OPS / slots
+    return {"bound": "alu", "unit": "state updates/s", "achieved": su_per_s, "peak": peak,
+            "frac": su_per_s / peak, "slots_per_state_update": slots,
+            "peak_lane_ops_per_s": VALU_PEAK_LANE_OPS,
+            "slots_per_state_update_measured": FWD_SLOTS_MEASURED,
+            "frac_at_measured_slots": su_per_s * FWD_SLOTS_MEASURED / VALU_PEAK_LANE_OPS,
+            "note": "fp32 VALU issue bound (unpacked, 256 CUs x 64 lanes x 2.4 GHz) at the "
+                    "algorithmic slots per state update; the measured-slots figure is how busy "
+                    "the kernel as built keeps the VALUs"}
 
 
 def algorithmic_bytes(w, which="fwd"):
@@ -83,7 +92,7 @@ def upload(s, dtype):
     import torch
     from paper_2506_15976_amd.inputs import fp32_to_bf16_bits
     out = {}
-    for k in FWD_KEYS:
+    for k in FWD_KEYS + ("dout",):
         v = s.get(k)
         if v is None:
             out[k] = None
@@ -92,6 +101,26 @@ def upload(s, dtype):
         else:
             out[k] = torch.from_numpy(v).to("cuda:0")
     return out
+
+
+def device_inputs(w, seed):
+    """One input set drawn on the GPU with the recipe of paper_2506_15976_amd.inputs
+    (x, Bm, Cm, z, dout ~ N(0,1); delta = 0.5 N(0,1); delta_bias = log(expm1(U[1e-3,
+    0.1])); A[d,n] = -(n+1); Dskip = 1), rounded to the storage type.  Used for the
+    rotation sets, which only have to be distinct memory with the same statistics."""
+    import torch
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(seed)
+    B, D, N, L = w["batch"], w["dim"], w["dstate"], w["seqlen"]
+    dt = torch.float32 if w["dtype"] == "fp32" else torch.bfloat16
+    rn = lambda *shape: torch.randn(*shape, device="cuda:0", generator=g)
+    s = dict(x=rn(B, D, L).to(dt), delta=(0.5 * rn(B, D, L)).to(dt),
+             A=-torch.arange(1, N + 1, device="cuda:0", dtype=torch.float32).repeat(D, 1).contiguous(),
+             Bm=rn(B, N, L).to(dt), Cm=rn(B, N, L).to(dt), Dskip=torch.ones(D, device="cuda:0"),
+             z=rn(B, D, L).to(dt),
+             delta_bias=torch.log(torch.expm1(torch.rand(D, device="cuda:0", generator=g) * 0.099 + 1e-3)),
+             dout=rn(B, D, L).to(dt))
+    return s
 
 
 def time_calls(calls, steps, warmup, per_launch=False):
@@ -123,15 +152,126 @@ def time_calls(calls, steps, warmup, per_launch=False):
     return region, {"mean": sum(per) / n, "median": per[n // 2], "min": per[0]}
 
 
+def measure_workload(lb, lib, name, w, sets, steps, warmup, with_bwd, per_launch=False):
+    """Times lbscan_fwd, lbscan_bidir_fwd, lbscan_bwd (alone, and after a forward call
+    that saved its checkpoints) on the rotating input sets.  Returns a dict of results
+    (times in ms)."""
+    import torch
+    from paper_2506_15976_amd import binding
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    nsets = len(sets)
+    ys = [torch.empty_like(s["x"]) for s in sets]
+    mk = lambda s, **kw: lb.make_args(**{k: s[k] for k in FWD_KEYS}, **kw)
+    fwd_args = [mk(s, window=w["window"], y=y) for s, y in zip(sets, ys)]
+    need = lb.lbscan_workspace_bytes(fwd_args[0], binding.WS_FWD)
+    ws_fwd = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
+    for ar in fwd_args:
+        ar.workspace, ar.workspace_bytes = ws_fwd.data_ptr(), need
+    fwd_calls = [(lambda ar=ar: lib.lbscan_fwd(ctypes.byref(ar), stream)) for ar in fwd_args]
+    rc = fwd_calls[0]()
+    assert rc == 0, f"lbscan_fwd failed: {rc}"
+    out = {}
+    if per_launch:
+        out["fwd_ms"], out["fwd_launch"] = time_calls(fwd_calls, steps, warmup, per_launch=True)
+        out["fwd_cache_hot_ms"] = time_calls(fwd_calls[:1], steps, warmup)
+    else:
+        out["fwd_ms"] = time_calls(fwd_calls, steps, warmup)
+
+    # two-pass global bi-directional scan on the same inputs (direction b = the
+    # (B,D,L)/(B,N,L) tensors of the next rotation slot: both passes read distinct memory)
+    bi_f = [mk(s, window=1, y=y) for s, y in zip(sets, ys)]
+    bi_b = [mk(sets[(i + 1) % nsets], window=1) for i in range(nsets)]
+    need = lb.lbscan_workspace_bytes(bi_f[0], binding.WS_BIDIR)
+    ws = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
+    for ar in bi_f:
+        ar.workspace, ar.workspace_bytes = ws.data_ptr(), need
+    bi_calls = [(lambda f=f, b=b: lib.lbscan_bidir_fwd(ctypes.byref(f), ctypes.byref(b), stream))
+                for f, b in zip(bi_f, bi_b)]
+    rc = bi_calls[0]()
+    assert rc == 0, f"lbscan_bidir_fwd failed: {rc}"
+    out["bidir_ms"] = time_calls(bi_calls, max(steps // 2, 1), max(warmup // 2, 1))
+
+    out["bwd_ms"] = out["fwd_plus_bwd_ms"] = None
+    if with_bwd:
+        g_args = []
+        for s_, ar in list(zip(sets, fwd_args))[:2]:     # two sets are enough to defeat the cache here
+            outs = [torch.empty_like(s_["x"]) for _ in range(3)] + [torch.empty_like(s_["Bm"]) for _ in range(2)] + \
+                   [torch.empty_like(s_["A"]), torch.empty_like(s_["Dskip"]), torch.empty_like(s_["delta_bias"])]
+            g_args.append((ar, s_["dout"], outs))
+        bneed = lb.lbscan_workspace_bytes(fwd_args[0], binding.WS_BWD)
+        ws_bwd = torch.empty(max(bneed // 4, 1), dtype=torch.float32, device="cuda:0")
+
+        def bwd_call(ar, dout, outs):
+            ar.workspace, ar.workspace_bytes = ws_bwd.data_ptr(), bneed
+            rc_ = lib.lbscan_bwd(ctypes.byref(ar), dout.data_ptr(), *[o.data_ptr() for o in outs], stream)
+            ar.workspace, ar.workspace_bytes = ws_fwd.data_ptr(), ws_fwd.numel() * 4
+            return rc_
+        assert bwd_call(*g_args[0]) == 0, "lbscan_bwd failed"
+        out["bwd_ms"] = time_calls([(lambda g=g: bwd_call(*g)) for g in g_args],
+                                   max(steps // 4, 1), max(warmup // 4, 1))
+        # training step: the forward call saves its checkpoints for the backward call
+        sneed = lb.lbscan_workspace_bytes(fwd_args[0], binding.WS_SAVED)
+        saved = torch.empty(max(sneed // 4, 1), dtype=torch.float32, device="cuda:0")
+
+        def train_call(ar, dout, outs):
+            if sneed:
+                ar.saved_state, ar.saved_state_bytes = saved.data_ptr(), sneed
+            r1 = lib.lbscan_fwd(ctypes.byref(ar), stream)
+            r2 = bwd_call(ar, dout, outs)
+            ar.saved_state, ar.saved_state_bytes = None, 0
+            return r1 or r2
+        assert train_call(*g_args[0]) == 0, "training step failed"
+        out["fwd_plus_bwd_ms"] = time_calls([(lambda g=g: train_call(*g)) for g in g_args],
+                                            max(steps // 4, 1), max(warmup // 4, 1))
+        # the plain Mamba scan (window 1) trained the same way: what the local backward
+        # scan adds to a training step (paper Appendix B compares the two kernels)
+        keepw = [ar.window for ar, _, _ in g_args]
+        for ar, _, _ in g_args:
+            ar.window = 1
+        assert train_call(*g_args[0]) == 0
+        out["fwd_plus_bwd_window1_ms"] = time_calls([(lambda g=g: train_call(*g)) for g in g_args],
+                                                    max(steps // 4, 1), max(warmup // 4, 1))
+        for (ar, _, _), m in zip(g_args, keepw):
+            ar.window = m
+    return out
+
+
+def summarize(name, w, r):
+    """Per-workload record of the "workloads" map."""
+    fb, bb = algorithmic_bytes(w, "fwd"), algorithmic_bytes(w, "bwd")
+    tokens = w["batch"] * w["seqlen"]
+    su = tokens * w["dim"] * w["dstate"]
+    rec = {
+        "shape": {k: w[k] for k in ("batch", "dim", "dstate", "seqlen", "window")},
+        "storage": w["dtype"], "arithmetic": "f32",
+        "fwd_ms": r["fwd_ms"], "fwd_tokens_per_s": tokens / (r["fwd_ms"] * 1e-3),
+        "fwd_algorithmic_bytes": fb, "fwd_gbps": fb / (r["fwd_ms"] * 1e-3) / 1e9,
+        "fwd_hbm_frac": fb / (r["fwd_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "fwd_alu_frac": su / (r["fwd_ms"] * 1e-3) / (VALU_PEAK_LANE_OPS / algorithmic_slots(w["window"])),
+        "fwd_traffic_bytes": MEASURED_TRAFFIC_BYTES.get(name),
+        "two_pass_bidir_ms": r["bidir_ms"], "speedup_vs_two_pass_bidir": r["bidir_ms"] / r["fwd_ms"],
+    }
+    if r.get("bwd_ms") is not None:
+        rec.update({
+            "bwd_ms": r["bwd_ms"], "bwd_algorithmic_bytes": bb,
+            "bwd_gbps": bb / (r["bwd_ms"] * 1e-3) / 1e9,
+            "bwd_hbm_frac": bb / (r["bwd_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "fwd_plus_bwd_ms": r["fwd_plus_bwd_ms"],
+            "fwd_plus_bwd_window1_ms": r.get("fwd_plus_bwd_window1_ms"),
+        })
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="vim_tiny")
+    ap.add_argument("--workload", default="vim_small", help="the workload of the headline figures")
     ap.add_argument("--shape", default="", help="B,D,N,L,M[,dtype]: time a custom shape instead of a named workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-bwd", action="store_true", help="skip the backward-pass timing")
+    ap.add_argument("--no-bwd", action="store_true", help="skip the backward-pass timings")
+    ap.add_argument("--no-others", action="store_true", help="only the headline workload (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--waves-log2", type=int, default=-1, help="force the state-split launch shape (tuning)")
@@ -146,7 +286,6 @@ def main():
     import numpy as np
     import torch
     import paper_2506_15976_amd as lb
-    from paper_2506_15976_amd import binding
     from paper_2506_15976_amd.inputs import BASE_SEED, WORKLOADS, make_inputs, make_workload
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -167,104 +306,57 @@ def main():
         a.workload = "custom"
     else:
         w = WORKLOADS[a.workload]
-    fwd_bytes = algorithmic_bytes(w, "fwd")
-    nsets = a.sets or max(2, int(np.ceil(640e6 / fwd_bytes)))
-    nsets = min(nsets, 16)
 
-    # independent input sets (same distribution, different seeds); set 0 is the named workload
-    sets, sets_b = [], []
+    def nsets_for(wl):
+        n = a.sets or max(2, int(np.ceil(640e6 / algorithmic_bytes(wl, "fwd"))))
+        return min(n, 12)
+
+    # ---- headline workload: set 0 is the named workload drawn on the host (it also feeds
+    # the CPU baseline), the other rotation sets are drawn on the GPU
     host0 = (make_workload(a.workload) if not a.shape else
              make_inputs(w["batch"], w["dim"], w["dstate"], w["seqlen"], seed=BASE_SEED + 99, dtype=w["dtype"]))
-    for i in range(nsets):
-        s = host0 if i == 0 else make_inputs(w["batch"], w["dim"], w["dstate"], w["seqlen"],
-                                             seed=BASE_SEED + 100 * (i + 1) + w["idx"], dtype=w["dtype"])
-        sets.append(upload(s, w["dtype"]))
-    # second parameter set for the reverse direction of the two-pass comparison: the
-    # (B,D,L)/(B,N,L) tensors of another rotation slot, so both passes read distinct memory
-    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if host0.get("dout") is None:
+        host0["dout"] = np.random.default_rng(BASE_SEED + 7).standard_normal(host0["x"].shape, dtype=np.float32)
+        if w["dtype"] == "bf16":
+            from paper_2506_15976_amd.inputs import round_to_bf16
+            host0["dout"] = round_to_bf16(host0["dout"])
+    nsets = nsets_for(w)
+    sets = [upload(host0, w["dtype"])] + [device_inputs(w, BASE_SEED + 100 * (i + 1) + w["idx"])
+                                          for i in range(1, nsets)]
+    head = measure_workload(lb, lib, a.workload, w, sets, a.steps, a.warmup, not a.no_bwd, per_launch=True)
+    del sets
+    torch.cuda.empty_cache()
 
-    ys = [torch.empty_like(s["x"]) for s in sets]
-    fwd_args = [lb.make_args(**s, window=w["window"], y=y) for s, y in zip(sets, ys)]
-    need = lb.lbscan_workspace_bytes(fwd_args[0], binding.WS_FWD)
-    ws_fwd = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
-    for ar in fwd_args:
-        ar.workspace, ar.workspace_bytes = ws_fwd.data_ptr(), need
-    fwd_calls = [(lambda ar=ar: lib.lbscan_fwd(ctypes.byref(ar), stream)) for ar in fwd_args]
-    rc = fwd_calls[0]()
-    assert rc == 0, f"lbscan_fwd failed: {rc}"
+    # ---- the other named workloads
+    workloads = {a.workload: summarize(a.workload, w, head)}
+    if not a.no_others and not a.shape:
+        for name, wl in WORKLOADS.items():
+            if name in (a.workload, "tiny"):
+                continue
+            ss = [device_inputs(wl, BASE_SEED + 100 * (i + 1) + wl["idx"]) for i in range(nsets_for(wl))]
+            r = measure_workload(lb, lib, name, wl, ss, max(a.steps // 2, 1), max(a.warmup // 2, 1), not a.no_bwd)
+            workloads[name] = summarize(name, wl, r)
+            del ss
+            torch.cuda.empty_cache()
 
-    ms_fwd, ms_kernel = time_calls(fwd_calls, a.steps, a.warmup, per_launch=True)
-    ms_hot = time_calls(fwd_calls[:1], a.steps, a.warmup)
-
-    # two-pass global bi-directional scan on the same inputs (direction b = next slot)
-    bi_f = [lb.make_args(**s, window=1, y=y) for s, y in zip(sets, ys)]
-    bi_b = [lb.make_args(**sets[(i + 1) % nsets], window=1) for i in range(nsets)]
-    need = lb.lbscan_workspace_bytes(bi_f[0], binding.WS_BIDIR)
-    ws = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
-    for ar in bi_f:
-        ar.workspace, ar.workspace_bytes = ws.data_ptr(), need
-    bi_calls = [(lambda f=f, b=b: lib.lbscan_bidir_fwd(ctypes.byref(f), ctypes.byref(b), stream))
-                for f, b in zip(bi_f, bi_b)]
-    rc = bi_calls[0]()
-    assert rc == 0, f"lbscan_bidir_fwd failed: {rc}"
-    ms_bidir = time_calls(bi_calls, max(a.steps // 2, 1), max(a.warmup // 2, 1))
-
-    # backward pass (training shapes; timed for every workload as extra information)
-    ms_bwd = None
-    ms_train = None
-    if not a.no_bwd:
-        import torch
-        g_args, keep = [], []
-        for s_, ar in zip(sets, fwd_args):
-            dout = torch.randn_like(s_["x"])
-            outs = [torch.empty_like(s_["x"]) for _ in range(3)] + [torch.empty_like(s_["Bm"]) for _ in range(2)] + \
-                   [torch.empty_like(s_["A"]), torch.empty_like(s_["Dskip"]), torch.empty_like(s_["delta_bias"])]
-            keep.append((dout, outs))
-            g_args.append((ar, dout, outs))
-            if len(g_args) == 2:
-                break                    # two sets are enough to defeat the cache for these sizes
-        need = lb.lbscan_workspace_bytes(fwd_args[0], binding.WS_BWD)
-        ws_bwd = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
-
-        def bwd_call(ar, dout, outs):
-            ar.workspace, ar.workspace_bytes = ws_bwd.data_ptr(), need
-            rc_ = lib.lbscan_bwd(ctypes.byref(ar), dout.data_ptr(), *[o.data_ptr() for o in outs], stream)
-            ar.workspace, ar.workspace_bytes = ws_fwd.data_ptr(), ws_fwd.numel() * 4
-            return rc_
-        assert bwd_call(*g_args[0]) == 0, "lbscan_bwd failed"
-        ms_bwd = time_calls([(lambda g=g: bwd_call(*g)) for g in g_args], max(a.steps // 4, 1), max(a.warmup // 4, 1))
-        # training step with the forward call saving checkpoints for the backward call
-        sneed = lb.lbscan_workspace_bytes(fwd_args[0], binding.WS_SAVED)
-        if sneed:
-            saved = torch.empty(sneed // 4, dtype=torch.float32, device="cuda:0")
-
-            def train_call(ar, dout, outs):
-                ar.saved_state, ar.saved_state_bytes = saved.data_ptr(), sneed
-                r1 = lib.lbscan_fwd(ctypes.byref(ar), stream)
-                r2 = bwd_call(ar, dout, outs)
-                ar.saved_state, ar.saved_state_bytes = None, 0
-                return r1 or r2
-        else:
-            def train_call(ar, dout, outs):
-                return lib.lbscan_fwd(ctypes.byref(ar), stream) or bwd_call(ar, dout, outs)
-        assert train_call(*g_args[0]) == 0, "training step failed"
-        ms_train = time_calls([(lambda g=g: train_call(*g)) for g in g_args], max(a.steps // 4, 1), max(a.warmup // 4, 1))
-
-    # the block's pre-scan step (depthwise causal conv + SiLU, width 4) on the same x
-    # tensors: an HBM-bound kernel of the same library, timed as extra information
+    # the block's pre-scan step (depthwise causal conv + SiLU, width 4) on x tensors of the
+    # headline shape: an HBM-bound kernel of the same library, timed as extra information
+    xs = [torch.randn(w["batch"], w["dim"], w["seqlen"], device="cuda:0").to(
+        torch.float32 if w["dtype"] == "fp32" else torch.bfloat16) for _ in range(3)]
+    ysc = [torch.empty_like(x) for x in xs]
     wconv = torch.randn(w["dim"], 4, device="cuda:0") * 0.5
     bconv = torch.randn(w["dim"], device="cuda:0")
-    conv_sets = list(zip(sets, ys))[:max(2, min(nsets, 4))]
-    conv_calls = [(lambda s_=s_, y_=y_: lb.lbscan_conv1d_fwd(s_["x"], wconv, bconv, out=y_)) for s_, y_ in conv_sets]
+    conv_calls = [(lambda x_=x_, y_=y_: lb.lbscan_conv1d_fwd(x_, wconv, bconv, out=y_)) for x_, y_ in zip(xs, ysc)]
     ms_conv = time_calls(conv_calls, max(a.steps // 4, 1), max(a.warmup // 4, 1))
     conv_bytes = 2 * w["batch"] * w["dim"] * w["seqlen"] * (2 if w["dtype"] == "bf16" else 4)
+    del xs, ysc
 
-    rates = None
+    ms_fwd = head["fwd_ms"]
+    fwd_bytes = algorithmic_bytes(w, "fwd")
     tokens = w["batch"] * w["seqlen"]
     # average launch duration over the timed region (includes the ~5 us gap between
     # dependent launches; an event pair per launch reads slightly more, a kernel trace less)
     gbps = fwd_bytes / (ms_fwd * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(a.workload)
 
     cpu = None
     if not a.no_cpu_baseline:
@@ -300,28 +392,33 @@ def main():
                "one_core_value": nb1 * w["seqlen"] / one_core,
                "one_core_sample": f"{nb1} batch entries, one call, {one_core:.3f} s"}
 
+    fl = head["fwd_launch"]
     line = {
         "metric": "lbscan_fwd_tokens_per_s", "value": tokens / (ms_fwd * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_fwd,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{a.workload}: B={w['batch']} D={w['dim']} N={w['dstate']} L={w['seqlen']} "
-                               f"M={w['window']} {w['dtype']} storage, forward", "input_sets_rotated": nsets},
+                               f"M={w['window']} {w['dtype']} storage, fp32 arithmetic, forward",
+                   "input_sets_rotated": nsets},
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": gbps / HBM_PEAK_GBPS, "traffic": traffic,
+                     "frac": gbps / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload),
                      "kernel": "rowlane_fwd_kernel", "algorithmic_bytes_per_launch": fwd_bytes,
-                     "launch_ms": ms_fwd, "launch_ms_event_pairs": ms_kernel["mean"],
-                     "launch_ms_median": ms_kernel["median"], "launch_ms_min": ms_kernel["min"]},
-        "alu_bound": alu_bound(tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3), rates),
+                     "launch_ms": ms_fwd, "launch_ms_event_pairs": fl["mean"],
+                     "launch_ms_median": fl["median"], "launch_ms_min": fl["min"]},
+        "alu_bound": alu_bound(tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3), w["window"]),
         "cpu_baseline": cpu,
-        "speedup_vs_two_pass_bidir": ms_bidir / ms_fwd,
-        "two_pass_bidir_ms": ms_bidir,
-        "cache_hot_ms_per_step": ms_hot,
-        "bwd_ms": ms_bwd,
-        "fwd_plus_bwd_ms": ms_train,
-        "bwd_algorithmic_gbps": None if ms_bwd is None else algorithmic_bytes(w, "bwd") / (ms_bwd * 1e-3) / 1e9,
+        "speedup_vs_two_pass_bidir": head["bidir_ms"] / ms_fwd,
+        "two_pass_bidir_ms": head["bidir_ms"],
+        "cache_hot_ms_per_step": head["fwd_cache_hot_ms"],
+        "bwd_ms": head["bwd_ms"],
+        "fwd_plus_bwd_ms": head["fwd_plus_bwd_ms"],
+        "fwd_plus_bwd_window1_ms": head.get("fwd_plus_bwd_window1_ms"),
+        "bwd_algorithmic_gbps": None if head["bwd_ms"] is None
+        else algorithmic_bytes(w, "bwd") / (head["bwd_ms"] * 1e-3) / 1e9,
         "prescan_conv_fwd_ms": ms_conv,
         "prescan_conv_fwd_gbps": conv_bytes / (ms_conv * 1e-3) / 1e9,
+        "workloads": workloads,
     }
     print(json.dumps(line))
 
