@@ -92,7 +92,7 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     p.yprev = nullptr; p.y = a->y; p.y_is_f32 = 0;
     p.force_waves_log2 = tuning_waves_log2();
     p.force_nseg = tuning_nseg();
-    p.nseg = 1; p.seg_tiles = 0; p.summary_only = 0; p.carry = nullptr; p.dsum = nullptr;
+    p.nseg = 1; p.seg_tiles = 0; p.summary_only = 0; p.fold_chain = 0; p.carry = nullptr; p.dsum = nullptr;
     p.ckpt = nullptr; p.cum = nullptr; p.dout = nullptr; p.psi = nullptr; p.gck = nullptr;
     p.h0 = a->h0; p.hT = a->hT;
     p.generic_window = 0; p.seg_tokens = 0;

@@ -37,7 +37,7 @@ carry_chain_kernel(float* __restrict__ carry, const float* __restrict__ dsum,
         const int ss = base + g;
         const bool on = ss < nseg;
         const int s = reverse ? nseg - 1 - (on ? ss : 0) : (on ? ss : 0);
-        const long k = (long)s * npairs + i;
+        const long k = ((long)s * N + n) * rows + row;        // (segment, n, row)
         // lanes past the end of the chain, and segments whose summary was not
         // computed (ss >= nsum: the last one, which nothing follows), hold the
         // identity map

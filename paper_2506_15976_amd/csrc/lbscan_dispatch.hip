@@ -6,6 +6,9 @@ namespace {
 
 struct Shape { int waves_log2, nseg, seg_tiles; };
 
+// Up to this many segments the full forward pass folds the carry chain itself.
+constexpr int kFoldChainSegments = 16;
+
 // The row-per-lane kernel runs one wave per (64 rows, state group, segment).
 // MI355X has 256 CUs x 4 SIMDs; the kernel needs a few waves per SIMD to cover
 // LDS and memory latency.
@@ -78,9 +81,10 @@ hipError_t launch_fwd(FwdParams p, void* workspace, float* saved, hipStream_t st
     p.nseg = s.nseg;
     p.seg_tiles = s.seg_tiles;
     p.summary_only = 0;
-    // uncut rows: the entering state is the (only) carried-in state
-    p.carry = const_cast<float*>(p.h0);
+    // (uncut rows read the entering state from h0)
+    p.carry = nullptr;
     p.dsum = nullptr;
+    p.fold_chain = 0;
     if (s.nseg > 1) {
         if (!workspace) return hipErrorInvalidValue;
         p.carry = static_cast<float*>(workspace);
@@ -89,8 +93,13 @@ hipError_t launch_fwd(FwdParams p, void* workspace, float* saved, hipStream_t st
         q.summary_only = 1;
         hipError_t e = launch(q);
         if (e != hipSuccess) return e;
-        e = launch_carry_chain(p, stream);
-        if (e != hipSuccess) return e;
+        // few segments: the full pass folds the chain itself (one launch less);
+        // many: the chain kernel, a shuffle scan over the segments
+        p.fold_chain = s.nseg <= kFoldChainSegments;
+        if (!p.fold_chain) {
+            e = launch_carry_chain(p, stream);
+            if (e != hipSuccess) return e;
+        }
     }
     return launch(p);
 }

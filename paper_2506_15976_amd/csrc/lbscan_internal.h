@@ -27,11 +27,12 @@ struct FwdParams {
     int force_waves_log2; // >= 0: override the state-split heuristic (tests, tuning)
     int force_nseg;       // >= 1: override the number of segments a row is cut into
     // Long rows are cut into nseg segments of seg_tiles forward tiles (kFwdTileTokens tokens each), one
-    // block per (64 rows, segment).  carry: (nseg, B*D, N) states entering each
+    // block per (64 rows, segment).  carry: (nseg, N, B*D) states entering each
     // segment (read by the full pass; written by the summary pass as the states a
     // segment reaches from zero); dsum: (nseg, B*D) sum of time steps per segment.
     int nseg, seg_tiles;
     int summary_only;
+    int fold_chain;       // full pass: fold the chain over the summaries in the kernel
     float* carry;         // nullable when nseg == 1
     float* dsum;
     // summary pass only: per-tile checkpoints for the backward pass (nullable):
