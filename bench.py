@@ -152,7 +152,7 @@ def time_calls(calls, steps, warmup, per_launch=False):
     return region, {"mean": sum(per) / n, "median": per[n // 2], "min": per[0]}
 
 
-def measure_workload(lb, lib, name, w, sets, steps, warmup, with_bwd, per_launch=False):
+def measure_workload(lb, lib, name, w, sets, steps, warmup, with_bwd, per_launch=False, grid=None):
     """Times lbscan_fwd, lbscan_bidir_fwd, lbscan_bwd (alone, and after a forward call
     that saved its checkpoints) on the rotating input sets.  Returns a dict of results
     (times in ms)."""
@@ -161,7 +161,7 @@ def measure_workload(lb, lib, name, w, sets, steps, warmup, with_bwd, per_launch
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     nsets = len(sets)
     ys = [torch.empty_like(s["x"]) for s in sets]
-    mk = lambda s, **kw: lb.make_args(**{k: s[k] for k in FWD_KEYS}, **kw)
+    mk = lambda s, **kw: lb.make_args(**{k: s[k] for k in FWD_KEYS}, grid=grid, **kw)
     fwd_args = [mk(s, window=w["window"], y=y) for s, y in zip(sets, ys)]
     need = lb.lbscan_workspace_bytes(fwd_args[0], binding.WS_FWD)
     ws_fwd = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
@@ -178,18 +178,22 @@ def measure_workload(lb, lib, name, w, sets, steps, warmup, with_bwd, per_launch
         out["fwd_ms"] = time_calls(fwd_calls, steps, warmup)
 
     # two-pass global bi-directional scan on the same inputs (direction b = the
-    # (B,D,L)/(B,N,L) tensors of the next rotation slot: both passes read distinct memory)
-    bi_f = [mk(s, window=1, y=y) for s, y in zip(sets, ys)]
-    bi_b = [mk(sets[(i + 1) % nsets], window=1) for i in range(nsets)]
-    need = lb.lbscan_workspace_bytes(bi_f[0], binding.WS_BIDIR)
-    ws = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
-    for ar in bi_f:
-        ar.workspace, ar.workspace_bytes = ws.data_ptr(), need
-    bi_calls = [(lambda f=f, b=b: lib.lbscan_bidir_fwd(ctypes.byref(f), ctypes.byref(b), stream))
-                for f, b in zip(bi_f, bi_b)]
-    rc = bi_calls[0]()
-    assert rc == 0, f"lbscan_bidir_fwd failed: {rc}"
-    out["bidir_ms"] = time_calls(bi_calls, max(steps // 2, 1), max(warmup // 2, 1))
+    # (B,D,L)/(B,N,L) tensors of the next rotation slot: both passes read distinct memory);
+    # stored order only
+    if grid is not None:
+        out["bidir_ms"] = None
+    bi_f = [] if grid is not None else [mk(s, window=1, y=y) for s, y in zip(sets, ys)]
+    if bi_f:
+        bi_b = [mk(sets[(i + 1) % nsets], window=1) for i in range(nsets)]
+        need = lb.lbscan_workspace_bytes(bi_f[0], binding.WS_BIDIR)
+        ws = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda:0")
+        for ar in bi_f:
+            ar.workspace, ar.workspace_bytes = ws.data_ptr(), need
+        bi_calls = [(lambda f=f, b=b: lib.lbscan_bidir_fwd(ctypes.byref(f), ctypes.byref(b), stream))
+                    for f, b in zip(bi_f, bi_b)]
+        rc = bi_calls[0]()
+        assert rc == 0, f"lbscan_bidir_fwd failed: {rc}"
+        out["bidir_ms"] = time_calls(bi_calls, max(steps // 2, 1), max(warmup // 2, 1))
 
     out["bwd_ms"] = out["fwd_plus_bwd_ms"] = None
     if with_bwd:
@@ -249,7 +253,8 @@ def summarize(name, w, r):
         "fwd_hbm_frac": fb / (r["fwd_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "fwd_alu_frac": su / (r["fwd_ms"] * 1e-3) / (VALU_PEAK_LANE_OPS / algorithmic_slots(w["window"])),
         "fwd_traffic_bytes": MEASURED_TRAFFIC_BYTES.get(name),
-        "two_pass_bidir_ms": r["bidir_ms"], "speedup_vs_two_pass_bidir": r["bidir_ms"] / r["fwd_ms"],
+        "two_pass_bidir_ms": r["bidir_ms"],
+        "speedup_vs_two_pass_bidir": None if r["bidir_ms"] is None else r["bidir_ms"] / r["fwd_ms"],
     }
     if r.get("bwd_ms") is not None:
         rec.update({
@@ -338,6 +343,17 @@ def main():
             workloads[name] = summarize(name, wl, r)
             del ss
             torch.cuda.empty_cache()
+
+        # the vertical scan of the Vim-small token grid (14 x 14 patches, class token last):
+        # the same kernels gathering token by token (paper Sec. 4.5 / Appendix D)
+        wl = WORKLOADS["vim_small"]
+        ss = [device_inputs(wl, BASE_SEED + 900 + i) for i in range(nsets_for(wl))]
+        r = measure_workload(lb, lib, "vim_small_columns", wl, ss, max(a.steps // 2, 1), max(a.warmup // 2, 1),
+                             not a.no_bwd, grid=(14, 14, 0))
+        workloads["vim_small_columns"] = dict(summarize("vim_small_columns", wl, r),
+                                              scan_order="columns of the 14 x 14 grid, class token last")
+        del ss
+        torch.cuda.empty_cache()
 
     # the block's pre-scan step (depthwise causal conv + SiLU, width 4) on x tensors of the
     # headline shape: an HBM-bound kernel of the same library, timed as extra information

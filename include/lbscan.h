@@ -100,7 +100,23 @@ typedef struct lbscan_args {
        enters at t = L-1 and leaves after t = 0.  Not used by lbscan_bidir_fwd. */
     const float *h0;          /* (B,D,N) or NULL: zeros */
     float       *hT;          /* (B,D,N) out of lbscan_fwd, or NULL: not wanted */
+    /* Scan order of a row's tokens (the multi-direction models of Sec. 4.5 / Appendix D
+       scan a 2-D token grid also vertically).  LBSCAN_ORDER_SEQUENCE (0, the default of a
+       zeroed struct): the tokens as stored.  LBSCAN_ORDER_COLUMNS: the tokens
+       [grid_prefix, grid_prefix + grid_h * grid_w) are a grid_h x grid_w grid stored row by
+       row and are scanned column by column, top to bottom; tokens before and after the
+       grid (class tokens) are scanned in place, before and after it.  The operator is
+       applied to the sequence in that order and every (B,D,L) / (B,N,L) tensor, inputs
+       and outputs alike, stays in stored order: no reordered copy exists.  reverse = 1
+       reverses the scanned sequence.  Kernels then gather token by token.  lbscan_fwd
+       with a window length outside {1,2,4,8,16} and lbscan_bidir_fwd support only the
+       stored order (LBSCAN_EUNSUPPORTED otherwise); lbscan_bwd supports every window. */
+    int32_t scan_order;
+    int32_t grid_h, grid_w, grid_prefix;
 } lbscan_args;
+
+#define LBSCAN_ORDER_SEQUENCE 0
+#define LBSCAN_ORDER_COLUMNS  1
 
 #define LBSCAN_WS_FWD   0
 #define LBSCAN_WS_BWD   1

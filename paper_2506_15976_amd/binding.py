@@ -37,6 +37,8 @@ class LbscanArgs(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("saved_state", ctypes.c_void_p), ("saved_state_bytes", ctypes.c_size_t),
         ("h0", ctypes.c_void_p), ("hT", ctypes.c_void_p),
+        ("scan_order", ctypes.c_int32), ("grid_h", ctypes.c_int32), ("grid_w", ctypes.c_int32),
+        ("grid_prefix", ctypes.c_int32),
     ]
 
 
@@ -131,12 +133,16 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
+ORDER_SEQUENCE, ORDER_COLUMNS = 0, 1
+
+
 def make_args(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, window,
               delta_softplus=True, reverse=False, y=None, workspace=None, saved_state=None,
-              h0=None, hT=None):
+              h0=None, hT=None, grid=None):
     """Fill a struct lbscan_args from device tensors.  Shapes: x, delta, z, y
     (B,D,L); Bm, Cm (B,N,L); A (D,N) fp32; Dskip, delta_bias (D) fp32; h0, hT
-    (B,D,N) fp32."""
+    (B,D,N) fp32.  grid = (H, W) or (H, W, prefix): scan the H x W token grid that
+    starts at token `prefix` column by column (see include/lbscan.h)."""
     import torch
     Bsz, D, L = x.shape
     N = A.shape[1]
@@ -165,6 +171,10 @@ def make_args(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, windo
                    _ptr(saved_state),
                    0 if saved_state is None else saved_state.numel() * saved_state.element_size(),
                    _ptr(h0), _ptr(hT))
+    if grid is not None:
+        a.scan_order = ORDER_COLUMNS
+        a.grid_h, a.grid_w = int(grid[0]), int(grid[1])
+        a.grid_prefix = int(grid[2]) if len(grid) > 2 else 0
     return a
 
 
@@ -229,7 +239,7 @@ def lbscan_saved_state(x, A, *, window):
 
 def lbscan_fwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, window,
                delta_softplus=True, reverse=False, out=None, stream=None, saved_state=None,
-               h0=None, return_state=False):
+               h0=None, return_state=False, grid=None):
     """out = locally bi-directional scan of the inputs (see include/lbscan.h).
     h0 (B,D,N) fp32: forward state entering the call; with return_state the result
     is (out, hT), hT the state that leaves it."""
@@ -240,7 +250,7 @@ def lbscan_fwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, wind
         hT = torch.empty((x.shape[0], x.shape[1], A.shape[1]), dtype=torch.float32, device=x.device)
     a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
                   delta_softplus=delta_softplus, reverse=reverse, y=y, saved_state=saved_state,
-                  h0=h0, hT=hT)
+                  h0=h0, hT=hT, grid=grid)
     ws = _workspace_for(a, WS_FWD, x, stream)
     _tie_to_stream(stream, y if out is None else None, hT)
     _check(load().lbscan_fwd(ctypes.byref(a), _stream(stream)), "lbscan_fwd")
@@ -283,14 +293,15 @@ def lbscan_bidir_fwd(set_f: dict, set_b: dict, *, out=None, stream=None):
 
 def lbscan_bwd(x, delta, A, Bm, Cm, Dskip=None, z=None, delta_bias=None, *, dout, window,
                delta_softplus=True, reverse=False, stream=None, saved_state=None,
-               h0=None, dhT=None):
+               h0=None, dhT=None, grid=None):
     """Gradients of lbscan_fwd.  Returns a dict: dx, ddelta, dz, dBm, dCm, dA,
     dDskip, ddelta_bias (None where the input is absent); with h0 or dhT (the
     gradient arriving at the state that left the forward call) also dh0, through
     lbscan_bwd_state."""
     import torch
     a = make_args(x, delta, A, Bm, Cm, Dskip, z, delta_bias, window=window,
-                  delta_softplus=delta_softplus, reverse=reverse, saved_state=saved_state, h0=h0)
+                  delta_softplus=delta_softplus, reverse=reverse, saved_state=saved_state, h0=h0,
+                  grid=grid)
     _check_like("dout", dout, x)
     g = dict(
         dx=torch.empty_like(x), ddelta=torch.empty_like(x),

@@ -49,6 +49,11 @@ int check_args_sizes(const lbscan_args* a, bool* empty)
     if (a->dstate > LBSCAN_MAX_DSTATE) return LBSCAN_EUNSUPPORTED;
     if (a->reverse != 0 && a->reverse != 1) return LBSCAN_EINVAL;
     if (a->seqlen > (1 << 24)) return LBSCAN_EUNSUPPORTED;   // 64 rows * L is indexed in 32 bits
+    if (a->scan_order != LBSCAN_ORDER_SEQUENCE && a->scan_order != LBSCAN_ORDER_COLUMNS) return LBSCAN_EINVAL;
+    if (a->scan_order == LBSCAN_ORDER_COLUMNS) {
+        if (a->grid_h < 1 || a->grid_w < 1 || a->grid_prefix < 0) return LBSCAN_EINVAL;
+        if ((long)a->grid_prefix + (long)a->grid_h * a->grid_w > (long)a->seqlen) return LBSCAN_EINVAL;
+    }
     if ((long)a->batch * a->dim * a->seqlen == 0) *empty = true;
     // a state size of zero with steps to take (y = Dskip x SiLU(z)) has no kernel
     if (!*empty && a->dstate == 0) return LBSCAN_EUNSUPPORTED;
@@ -87,6 +92,12 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     lbscan::FwdParams p;
     p.batch = a->batch; p.dim = a->dim; p.dstate = a->dstate; p.seqlen = a->seqlen;
     p.window = window; p.dtype = a->dtype; p.softplus = a->delta_softplus; p.reverse = a->reverse;
+    p.order.kind = a->scan_order;
+    p.order.prefix = a->grid_prefix;
+    p.order.H = a->scan_order ? a->grid_h : 1;
+    p.order.W = a->scan_order ? a->grid_w : 1;
+    p.order.HW = p.order.H * p.order.W;
+    p.order.rH = 1.0f / (float)p.order.H;
     p.x = a->x; p.delta = a->delta; p.Bm = a->Bm; p.Cm = a->Cm; p.z = a->z;
     p.A = a->A; p.Dskip = a->Dskip; p.bias = a->delta_bias;
     p.yprev = nullptr; p.y = a->y; p.y_is_f32 = 0;
@@ -195,6 +206,7 @@ int fwd_with_scratch(const lbscan_args* args, void* scratch, size_t scratch_byte
     const int M = effective_window(args->window, args->seqlen);
     if (M == 0) {
         // no compiled kernel for this window length: the two-launch path
+        if (args->scan_order != LBSCAN_ORDER_SEQUENCE) return LBSCAN_EUNSUPPORTED;
         lbscan::FwdParams p = to_params(args, args->window < args->seqlen ? args->window : args->seqlen);
         const size_t need = lbscan::fwd_generic_workspace_bytes(p);
         if (need && (!scratch || scratch_bytes < need || !aligned4(scratch)))
@@ -230,6 +242,8 @@ int lbscan_bidir_fwd(const lbscan_args* fs, const lbscan_args* bs, void* hip_str
     if (fs->batch != bs->batch || fs->dim != bs->dim || fs->dstate != bs->dstate ||
         fs->seqlen != bs->seqlen || fs->dtype != bs->dtype) return LBSCAN_EINVAL;
     if (fs->h0 || fs->hT || bs->h0 || bs->hT) return LBSCAN_EINVAL;   // whole sequences only
+    if (fs->scan_order != LBSCAN_ORDER_SEQUENCE || bs->scan_order != LBSCAN_ORDER_SEQUENCE)
+        return LBSCAN_EUNSUPPORTED;
     if (empty_f) return LBSCAN_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
@@ -306,6 +320,7 @@ int lbscan_bwd_state(const lbscan_args* a, const void* dout, const float* dhT,
     lbscan::BwdParams p;
     p.batch = f.batch; p.dim = f.dim; p.dstate = f.dstate; p.seqlen = f.seqlen;
     p.window = M; p.dtype = f.dtype; p.softplus = f.softplus; p.reverse = f.reverse;
+    p.order = f.order;
     p.x = f.x; p.delta = f.delta; p.Bm = f.Bm; p.Cm = f.Cm; p.z = f.z;
     p.A = f.A; p.Dskip = f.Dskip; p.bias = f.bias;
     p.dout = dout; p.dx = dx; p.ddelta = ddelta; p.dz = a->z ? dz : nullptr;

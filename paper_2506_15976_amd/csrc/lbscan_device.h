@@ -46,6 +46,30 @@ __device__ __forceinline__ float sigmoid_f32(float v)
     return fast_rcp(1.0f + fast_exp2(-v * kLog2e));
 }
 
+// ---- scan order ------------------------------------------------------------
+// The order in which a row's tokens are scanned: index t of the scanned sequence ->
+// index of the token as stored.  kind 0: the tokens as stored.  kind 1: the tokens
+// [prefix, prefix + H W) are an H x W grid stored row by row and are scanned column
+// by column, top to bottom (the vertical scans of the multi-direction models of
+// Sec. 4.5 / Appendix D); tokens before and after the grid (class tokens) keep
+// their places.  Set by the host; H > 0 also for kind 0.
+struct TokenOrder {
+    int kind, prefix, H, W, HW;
+    float rH;          // 1 / H
+    __device__ __forceinline__ int operator()(int t) const
+    {
+        if (kind == 0) return t;
+        const int k = t - prefix;
+        if (k < 0 || k >= HW) return t;
+        // column c = k / H: the float quotient is off by at most one for k < 2^24
+        int c = (int)((float)k * rH);
+        int r = k - c * H;
+        if (r < 0) { r += H; --c; }
+        if (r >= H) { r -= H; ++c; }
+        return prefix + r * W + c;
+    }
+};
+
 // ---- storage types -------------------------------------------------------
 struct bf16_t { uint16_t bits; };
 
@@ -124,6 +148,23 @@ __device__ __forceinline__ Quad<T> quad_raw_checked(const T* __restrict__ base, 
     }
     return q;
 }
+// The same for a scan order: element e is the token ord(ph + e) of the row that
+// starts at base + off - ph.
+template <typename T>
+__device__ __forceinline__ Quad<T> quad_raw_checked(const T* __restrict__ base, long off, int ph, int L,
+                                                    const TokenOrder& ord)
+{
+    if (ord.kind == 0) return quad_raw_checked<T>(base, off, ph, L);
+    Quad<T> q;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int t = ph + e;
+        const int tc = t < 0 ? 0 : (t >= L ? L - 1 : t);
+        const T v = base[(off - ph) + ord(tc)];
+        q.v[e] = (t == tc) ? v : zero_elem<T>();
+    }
+    return q;
+}
 
 // The same result as quad_raw_checked with ONE quad load, for rows of at least four
 // tokens that allow quad loads: the quad is loaded from the nearest position that
@@ -164,6 +205,16 @@ __device__ __forceinline__ void quad_store(T* __restrict__ base, long off, bool 
         for (int e = 0; e < 4; ++e)
             if (ph + e >= 0 && ph + e < L) base[off + e] = from_f32<T>(in[e]);
     }
+}
+// The same for a scan order (never fast then: the four tokens are not neighbours).
+template <typename T>
+__device__ __forceinline__ void quad_store(T* __restrict__ base, long off, bool fast,
+                                           int ph, int L, const float in[4], const TokenOrder& ord)
+{
+    if (ord.kind == 0) { quad_store<T>(base, off, fast, ph, L, in); return; }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (ph + e >= 0 && ph + e < L) base[(off - ph) + ord(ph + e)] = from_f32<T>(in[e]);
 }
 
 }  // namespace lbscan

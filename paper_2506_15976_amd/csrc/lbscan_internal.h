@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "lbscan_device.h"
+
 namespace lbscan {
 
 // Arguments of one forward launch, already validated by the C entry points.
@@ -13,6 +15,7 @@ struct FwdParams {
     int dtype;     // LBSCAN_FP32 / LBSCAN_BF16
     int softplus;
     int reverse;
+    TokenOrder order;   // scan order of a row's tokens (kind 0: as stored)
     const void* x;
     const void* delta;
     const void* Bm;
@@ -64,6 +67,7 @@ struct BwdParams {
     int dtype;
     int softplus;
     int reverse;
+    TokenOrder order;
     const void* x;
     const void* delta;
     const void* Bm;

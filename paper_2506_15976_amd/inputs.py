@@ -92,6 +92,20 @@ def make_workload(name: str, *, direction_b: bool = False):
     return s
 
 
+def column_order(seqlen: int, grid_h: int, grid_w: int, prefix: int = 0) -> np.ndarray:
+    """Index array perm with scanned[j] = stored[perm[j]] for the column-by-column scan
+    of a grid_h x grid_w token grid stored row by row at tokens [prefix, prefix + H W);
+    tokens outside the grid keep their places.  (An index permutation only: the tests
+    reorder inputs with it, run the oracle in plain sequence order and put the outputs
+    back.)"""
+    perm = np.arange(seqlen)
+    hw = grid_h * grid_w
+    assert prefix >= 0 and prefix + hw <= seqlen
+    k = np.arange(hw)
+    perm[prefix:prefix + hw] = prefix + (k % grid_h) * grid_w + k // grid_h
+    return perm
+
+
 def error_metric(got: np.ndarray, ref: np.ndarray, floor_frac: float = 0.1) -> float:
     """Scale-aware maximum relative error:
         max_i |got_i - ref_i| / max(|ref_i|, floor_frac * rms(ref)).

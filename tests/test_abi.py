@@ -35,7 +35,9 @@ def test_every_declared_symbol_is_exported(lib):
 def test_struct_layout_matches_header():
     from paper_2506_15976_amd.binding import LbscanArgs
     # 8 int32 + 9 pointers + (workspace pointer, size_t) + (saved_state pointer, size_t)
-    assert ctypes.sizeof(LbscanArgs) == 8 * 4 + 10 * 8 + 8 + 16 + 16
+    # + h0, hT + 4 int32 (scan order)
+    assert ctypes.sizeof(LbscanArgs) == 8 * 4 + 10 * 8 + 8 + 16 + 16 + 16
+    assert LbscanArgs.scan_order.offset == 32 + 15 * 8
     assert LbscanArgs.x.offset == 32
     from paper_2506_15976_amd.binding import LbscanConvArgs
     # 7 int32 (padded to 32 bytes) + 4 pointers
