@@ -173,6 +173,30 @@ __device__ __forceinline__ Quad<T> quad_raw_checked(const T* __restrict__ base, 
 // loads cost the texture-address unit one pass per element (a wave's 64 dwords sit
 // in up to 64 different sectors), which made the ragged last tile of a row as
 // expensive as a full one.
+// Two steps, so that the load can stay in flight: quad_raw_clamped issues it,
+// quad_rearrange (when the data is needed) moves the elements.
+template <typename T>
+__device__ __forceinline__ Quad<T> quad_raw_clamped(const T* __restrict__ base, long off, int ph, int L)
+{
+    const int phc = ph < 0 ? 0 : (ph > L - 4 ? L - 4 : ph);
+    return *reinterpret_cast<const Quad<T>*>(base + (off + (phc - ph)));
+}
+template <typename T>
+__device__ __forceinline__ Quad<T> quad_rearrange(const Quad<T>& q, int ph, int L)
+{
+    const int phc = ph < 0 ? 0 : (ph > L - 4 ? L - 4 : ph);
+    const int s = ph - phc;                       // wanted element e is loaded element e + s
+    Quad<T> r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int k = e + s;
+        T v = zero_elem<T>();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v = (k == j) ? q.v[j] : v;
+        r.v[e] = v;
+    }
+    return r;
+}
 template <typename T>
 __device__ __forceinline__ Quad<T> quad_raw_ragged(const T* __restrict__ base, long off, int ph, int L)
 {

@@ -113,7 +113,10 @@ struct ConvParams {
 };
 
 constexpr int kTileTokens = 16;      // tokens per tile of the backward kernel = checkpoint spacing
-constexpr int kFwdTileTokens = 32;   // tokens per tile of the forward kernel (128 bytes of an fp32 row)
+#ifndef LBSCAN_FWD_TILE
+#define LBSCAN_FWD_TILE 32
+#endif
+constexpr int kFwdTileTokens = LBSCAN_FWD_TILE;   // tokens per tile of the forward kernel (32: 128 bytes of an fp32 row)
 
 // Window lengths with a compiled kernel.
 inline bool window_supported(int M) { return M == 1 || M == 2 || M == 4 || M == 8 || M == 16; }
