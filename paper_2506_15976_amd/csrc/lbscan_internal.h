@@ -112,7 +112,10 @@ struct ConvParams {
     int items_per_wave;   // set by the launcher
 };
 
-constexpr int kTileTokens = 16;      // tokens per tile of the backward kernel = checkpoint spacing
+#ifndef LBSCAN_BWD_TILE
+#define LBSCAN_BWD_TILE 16
+#endif
+constexpr int kTileTokens = LBSCAN_BWD_TILE;      // tokens per tile of the backward kernel = checkpoint spacing
 #ifndef LBSCAN_FWD_TILE
 #define LBSCAN_FWD_TILE 32
 #endif
