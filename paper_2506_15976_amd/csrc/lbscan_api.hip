@@ -34,6 +34,7 @@ int scratch_too_small(size_t need, size_t have, bool fixed)
 std::atomic<int> g_waves_log2{-1};
 std::atomic<int> g_nseg{0};
 int tuning_waves_log2() { return g_waves_log2.load(std::memory_order_relaxed); }
+std::atomic<int> g_mapping{0};
 int tuning_nseg() { return g_nseg.load(std::memory_order_relaxed); }
 
 bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
@@ -103,6 +104,7 @@ lbscan::FwdParams to_params(const lbscan_args* a, int window)
     p.yprev = nullptr; p.y = a->y; p.y_is_f32 = 0;
     p.force_waves_log2 = tuning_waves_log2();
     p.force_nseg = tuning_nseg();
+    p.force_mapping = g_mapping.load(std::memory_order_relaxed);
     p.nseg = 1; p.seg_tiles = 0; p.summary_only = 0; p.fold_chain = 0; p.carry = nullptr; p.dsum = nullptr;
     p.ckpt = nullptr; p.cum = nullptr; p.dout = nullptr; p.psi = nullptr; p.gck = nullptr;
     p.h0 = a->h0; p.hT = a->hT;
@@ -423,6 +425,11 @@ int lbscan_set_option(const char* name, int value)
     if (strcmp(name, "segments") == 0) {
         if (value < 0 || value > (1 << 20)) return LBSCAN_EINVAL;
         g_nseg.store(value, std::memory_order_relaxed);
+        return LBSCAN_OK;
+    }
+    if (strcmp(name, "mapping") == 0) {
+        if (value < 0 || value > 2) return LBSCAN_EINVAL;
+        g_mapping.store(value, std::memory_order_relaxed);
         return LBSCAN_OK;
     }
     return LBSCAN_EINVAL;

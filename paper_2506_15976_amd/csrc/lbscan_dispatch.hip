@@ -50,6 +50,22 @@ size_t carry_floats(const FwdParams& p, int nseg)
     return (size_t)nseg * p.batch * p.dim * (size_t)p.dstate;
 }
 
+// The chunk-per-lane kernel takes over where the row-per-lane kernels would have
+// to cut rows into segments (a second read and ~60% more arithmetic) although
+// there are rows enough to fill the chip with one wave per row: long rows, many
+// of them.  It leaves no checkpoints for a backward call.
+bool use_chunk_mapping(const FwdParams& p, const Shape& s, const float* saved)
+{
+    if (p.force_mapping == 1) return false;
+    FwdParams q = p;
+    q.ckpt = nullptr; q.summary_only = 0;
+    if (!fwd_chunk_supported(q)) return false;
+    if (saved && s.nseg == 1) return false;
+    if (p.force_mapping == 2) return true;
+    const long rows = (long)p.batch * p.dim;
+    return s.nseg > 1 && rows >= 4096 && p.seqlen >= 2048;
+}
+
 }  // namespace
 
 size_t fwd_workspace_bytes(const FwdParams& p)
@@ -72,6 +88,7 @@ hipError_t launch_fwd(FwdParams p, void* workspace, float* saved, hipStream_t st
 {
     if (p.batch == 0 || p.dim == 0 || p.seqlen == 0) return hipSuccess;
     const Shape s = pick_shape(p);
+    if (use_chunk_mapping(p, s, saved)) return launch_fwd_chunk(p, stream);
     p.ckpt = (saved && s.nseg == 1) ? saved : nullptr;
     p.cum = nullptr;
     auto launch = [&](const FwdParams& q) {

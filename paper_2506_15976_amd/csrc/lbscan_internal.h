@@ -29,6 +29,7 @@ struct FwdParams {
     int y_is_f32;         // write y as fp32 whatever dtype says (first pass of the two-pass scan)
     int force_waves_log2; // >= 0: override the state-split heuristic (tests, tuning)
     int force_nseg;       // >= 1: override the number of segments a row is cut into
+    int force_mapping;    // 0: heuristic; 1: row-per-lane kernels; 2: chunk-per-lane kernel where it applies
     // Long rows are cut into nseg segments of seg_tiles forward tiles (kFwdTileTokens tokens each), one
     // block per (64 rows, segment).  carry: (nseg, N, B*D) states entering each
     // segment (read by the full pass; written by the summary pass as the states a
@@ -128,6 +129,11 @@ inline bool window_supported(int M) { return M == 1 || M == 2 || M == 4 || M == 
 // unit per storage type.  waves_log2: log2 of the waves the states are split over.
 hipError_t launch_fwd_rowlane_f32(const FwdParams& p, int waves_log2, hipStream_t stream);
 hipError_t launch_fwd_rowlane_bf16(const FwdParams& p, int waves_log2, hipStream_t stream);
+
+// Chunk-per-lane forward kernel (lbscan_fwd_chunk.hip): one wave per row, 16 tokens
+// per lane, no workspace.  fwd_chunk_supported: p is within what it implements.
+bool fwd_chunk_supported(const FwdParams& p);
+hipError_t launch_fwd_chunk(const FwdParams& p, hipStream_t stream);
 
 // Picks the launch shape for the sizes in p and launches the forward pass
 // (several kernels when rows are cut into segments).  workspace must hold
