@@ -189,8 +189,10 @@ chunk_fwd_kernel(const FwdParams p)
     put_bc(0, load_bc(0, 0));
     __syncthreads();
 
-    // the time steps and x of a chunk are fetched during the last state of the chunk
-    // before, z during the last state of its own chunk
+    // the time steps of a chunk are fetched during the last state of the chunk before
+    // and its x while that chunk's result is stored; z during the chunk's own last state
+    // (fp32 quads are twice the registers: there the time steps wait for the store phase too)
+    constexpr bool kEarlyDt = sizeof(T) == 2;
     RowQuads qd = issue_row(dg, 0), qx = issue_row(xg, 0), qz;
     for (int chunk = 0; chunk < nchunks; ++chunk) {
         const int t_lane = chunk * kChunk + lane * kP;          // this lane's first token
@@ -198,13 +200,13 @@ chunk_fwd_kernel(const FwdParams p)
         {
             float xv[kP];
             turn_row(qd, dt);
-            turn_row(qx, xv);
 #pragma unroll
             for (int k = 0; k < kP; ++k) dt[k] += bias;
             if (p.softplus) {
 #pragma unroll
                 for (int k = 0; k < kP; ++k) dt[k] = softplus_f32(dt[k]);
             }
+            turn_row(qx, xv);
             // tokens past the end of the row: identity steps (abar = 1, u = 0)
             if (!chunk_is_whole(chunk)) {
 #pragma unroll
@@ -227,7 +229,7 @@ chunk_fwd_kernel(const FwdParams p)
             if (more) nxt = n + 1 < N ? load_bc(chunk, n + 1) : load_bc(chunk + 1, 0);
             if constexpr (LAST) {
                 if (zg) qz = issue_row(zg, chunk);
-                if (chunk + 1 < nchunks) { qd = issue_row(dg, chunk + 1); qx = issue_row(xg, chunk + 1); }
+                if constexpr (kEarlyDt) { if (chunk + 1 < nchunks) qd = issue_row(dg, chunk + 1); }
             }
 
             if (row_ok) {
@@ -309,6 +311,10 @@ chunk_fwd_kernel(const FwdParams p)
             *reinterpret_cast<float4*>(&wbuf[lane * kPitch + 4 * g]) =
                 make_float4(y[4 * g], y[4 * g + 1], y[4 * g + 2], y[4 * g + 3]);
         wave_sync_lds();
+        if (chunk + 1 < nchunks) {
+            if constexpr (!kEarlyDt) qd = issue_row(dg, chunk + 1);
+            qx = issue_row(xg, chunk + 1);
+        }
         if (row_ok) {
             const bool whole = chunk_is_whole(chunk);
 #pragma unroll
