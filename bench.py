@@ -31,22 +31,43 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # at half rate on this chip (measured: 19.2 T/s against 38.6 T/s for fma, and the two do
 # not overlap), i.e. it takes two issue slots.
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
-# Issue slots per state update of the forward kernel as measured (SQ_INSTS_VALU +
-# SQ_INSTS_VALU_TRANS_F32, profiles/lbscan_counters_vim_small.md): secondary figure.
-FWD_SLOTS_MEASURED = 11.05
 FWD_KEYS = ("x", "delta", "A", "Bm", "Cm", "Dskip", "z", "delta_bias")
 
-# L2-to-fabric bytes per lbscan_fwd call from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# (KiB per dispatch, summed over the launches of one call), each scaled by what the
-# same counter reads for a plain elementwise kernel that reads and writes 1 GiB
-# (bench.py --copy-calibration: FETCH_SIZE x2.0, WRITE_SIZE x1.0); profiles/ has the runs.
-MEASURED_TRAFFIC_BYTES = {
-    "vim_tiny": int((42414.4 * 2.0 + 25978.7) * 1024),
-    "vim_small": int((234641.4 * 2.0 + 97432.1) * 1024),
-    # summary launch + carry chain + full pass
-    "hires_4096": int(((128629.7 + 73254.8 + 2357.1) * 2.0 + 58316.8 + 3265.7 + 3072.0) * 1024),
-    "wsi_bag": int(((116334.2 + 82034.2 + 12812.9) * 2.0 + 65552.7 + 3179.2 + 6014.8) * 1024),
+# Two figures come from the rocprofv3 summaries committed under profiles/ (counters
+# cannot be read from inside this program); both are None when the summary is absent.
+#  * L2-to-fabric bytes of one lbscan_fwd call: FETCH_SIZE and WRITE_SIZE (KiB per
+#    dispatch) summed over the launches of one call, each scaled by what the same
+#    counter reads for a plain elementwise kernel that reads and writes 1 GiB
+#    (--copy-calibration: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0);
+#  * issue slots per state update of the forward kernels as built (SQ_INSTS_VALU +
+#    SQ_INSTS_VALU_TRANS_F32): the secondary figure of alu_bound.
+_PROFILE_LINES = {
+    "traffic": ("lbscan_kernels_{}.md", r"lbscan_fwd call traffic: (\d+) bytes"),
+    "slots": ("lbscan_counters_{}.md", r"lbscan_fwd call issue slots per state update: ([0-9.]+)"),
 }
+
+
+# The launches of one lbscan_fwd call (the library's own choice at these shapes).
+FWD_KERNELS = {
+    "vim_tiny": "rowlane_fwd_kernel", "vim_small": "rowlane_fwd_kernel",
+    "hires_4096": "chunk_fwd_kernel",
+    "wsi_bag": "rowlane_fwd_kernel summary pass + carry_chain_kernel + rowlane_fwd_kernel full pass",
+}
+
+
+def profile_figure(kind, workload):
+    import re
+    fname, pattern = _PROFILE_LINES[kind]
+    if kind == "slots" and workload == "vim_tiny":
+        workload = "vim_small"          # the same kernel instance; counters were taken on vim_small
+    try:
+        text = open(os.path.join(ROOT, "profiles", fname.format(workload))).read()
+    except OSError:
+        return None
+    m = re.search(pattern, text)
+    if not m:
+        return None
+    return int(m.group(1)) if kind == "traffic" else float(m.group(1))
 
 
 def algorithmic_slots(window):
@@ -58,14 +79,15 @@ def algorithmic_slots(window):
     return 6.0 + (max(2 * m - 3, 0) / m if m >= 2 else 0.0)
 
 
-def alu_bound(su_per_s, window):
+def alu_bound(su_per_s, window, workload=None):
     slots = algorithmic_slots(window)
     peak = VALU_PEAK_LANE_OPS / slots
+    measured = profile_figure("slots", workload) if workload else None
     return {"bound": "alu", "unit": "state updates/s", "achieved": su_per_s, "peak": peak,
             "frac": su_per_s / peak, "slots_per_state_update": slots,
             "peak_lane_ops_per_s": VALU_PEAK_LANE_OPS,
-            "slots_per_state_update_measured": FWD_SLOTS_MEASURED,
-            "frac_at_measured_slots": su_per_s * FWD_SLOTS_MEASURED / VALU_PEAK_LANE_OPS,
+            "slots_per_state_update_measured": measured,
+            "frac_at_measured_slots": None if measured is None else su_per_s * measured / VALU_PEAK_LANE_OPS,
             "note": "fp32 VALU issue bound (unpacked, 256 CUs x 64 lanes x 2.4 GHz) at the "
                     "algorithmic slots per state update; the measured-slots figure is how busy "
                     "the kernel as built keeps the VALUs"}
@@ -176,6 +198,15 @@ def measure_workload(lb, lib, name, w, sets, steps, warmup, with_bwd, per_launch
         out["fwd_cache_hot_ms"] = time_calls(fwd_calls[:1], steps, warmup)
     else:
         out["fwd_ms"] = time_calls(fwd_calls, steps, warmup)
+    # the same call with the row-per-lane kernels forced (rows cut into segments), where
+    # the library itself picks the chunk-per-lane kernel
+    out["fwd_row_per_lane_ms"] = None
+    if w["dtype"] == "bf16" and w["seqlen"] >= 2048 and grid is None:
+        lb.lbscan_set_option("mapping", 1)
+        try:
+            out["fwd_row_per_lane_ms"] = time_calls(fwd_calls, max(steps // 2, 1), max(warmup // 2, 1))
+        finally:
+            lb.lbscan_set_option("mapping", 0)
 
     # two-pass global bi-directional scan on the same inputs (direction b = the
     # (B,D,L)/(B,N,L) tensors of the next rotation slot: both passes read distinct memory);
@@ -252,10 +283,12 @@ def summarize(name, w, r):
         "fwd_algorithmic_bytes": fb, "fwd_gbps": fb / (r["fwd_ms"] * 1e-3) / 1e9,
         "fwd_hbm_frac": fb / (r["fwd_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "fwd_alu_frac": su / (r["fwd_ms"] * 1e-3) / (VALU_PEAK_LANE_OPS / algorithmic_slots(w["window"])),
-        "fwd_traffic_bytes": MEASURED_TRAFFIC_BYTES.get(name),
+        "fwd_traffic_bytes": profile_figure("traffic", name),
         "two_pass_bidir_ms": r["bidir_ms"],
         "speedup_vs_two_pass_bidir": None if r["bidir_ms"] is None else r["bidir_ms"] / r["fwd_ms"],
     }
+    if r.get("fwd_row_per_lane_ms") is not None:
+        rec["fwd_row_per_lane_ms"] = r["fwd_row_per_lane_ms"]
     if r.get("bwd_ms") is not None:
         rec.update({
             "bwd_ms": r["bwd_ms"], "bwd_algorithmic_bytes": bb,
@@ -418,11 +451,12 @@ def main():
                                f"M={w['window']} {w['dtype']} storage, fp32 arithmetic, forward",
                    "input_sets_rotated": nsets},
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": gbps / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES.get(a.workload),
-                     "kernel": "rowlane_fwd_kernel", "algorithmic_bytes_per_launch": fwd_bytes,
+                     "frac": gbps / HBM_PEAK_GBPS, "traffic": profile_figure("traffic", a.workload),
+                     "kernel": FWD_KERNELS.get(a.workload, "rowlane_fwd_kernel"),
+                     "algorithmic_bytes_per_launch": fwd_bytes,
                      "launch_ms": ms_fwd, "launch_ms_event_pairs": fl["mean"],
                      "launch_ms_median": fl["median"], "launch_ms_min": fl["min"]},
-        "alu_bound": alu_bound(tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3), w["window"]),
+        "alu_bound": alu_bound(tokens * w["dim"] * w["dstate"] / (ms_fwd * 1e-3), w["window"], a.workload),
         "cpu_baseline": cpu,
         "speedup_vs_two_pass_bidir": head["bidir_ms"] / ms_fwd,
         "two_pass_bidir_ms": head["bidir_ms"],
