@@ -30,7 +30,7 @@
  * passed in (a hipStream_t cast to void*, NULL = default stream) and returns.
  * Outputs are fully overwritten.  Calls are re-entrant as long as
  * lbscan_set_option is not called concurrently: the only global state is a
- * thread-local last-error string and the two process-wide tuning options.
+ * thread-local last-error string and the process-wide tuning options.
  *
  * Errors: 0 on success, a negative LBSCAN_E* code otherwise; nothing is
  * enqueued when an error is returned before launch.
@@ -223,6 +223,15 @@ int lbscan_default_window(int32_t seqlen);
  *                 row is cut for parallel scanning (long rows, few channels);
  *                 k >= 1 asks for k (rounded so that segments are whole 32-token tiles).  It
  *                 changes lbscan_workspace_bytes: query after setting it.
+ *   "mapping":    0 (default) lets lbscan_fwd choose between its two kernel
+ *                 families: one lane per row (rows walked in tiles; cut into
+ *                 segments when rows are few) and one wave per row with 16 tokens
+ *                 per lane (the tile-per-thread organisation of Sec. 3.4; picked
+ *                 for long bf16 rows that are many).  1 forces the first, 2 the
+ *                 second wherever it applies (compiled window lengths, stored
+ *                 order, reverse = 0, rows that allow 16-byte accesses); other
+ *                 calls are not affected.  Results agree within the tolerance of
+ *                 the arithmetic; workspace sizes do not change.
  * Returns LBSCAN_EINVAL for an unknown name or a value out of range. */
 int lbscan_set_option(const char *name, int value);
 

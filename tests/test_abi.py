@@ -142,6 +142,8 @@ def test_workspace_sizes_follow_the_launch_plan(lib):
         assert lib.lbscan_set_option(b"segments", 0) == 0
     assert lib.lbscan_set_option(b"segments", -1) != 0
     assert lib.lbscan_set_option(b"waves_log2", 4) != 0
+    assert lib.lbscan_set_option(b"mapping", 3) != 0 and lib.lbscan_set_option(b"mapping", -1) != 0
+    assert lib.lbscan_set_option(b"mapping", 2) == 0 and lib.lbscan_set_option(b"mapping", 0) == 0
     assert lib.lbscan_set_option(b"no_such_option", 0) != 0
     assert lib.lbscan_set_option(None, 0) != 0
 

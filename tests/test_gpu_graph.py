@@ -30,15 +30,18 @@ def _workspace(lb, args, which, device):
     return ws
 
 
-@pytest.mark.parametrize("shape,window,segments", [((2, 70, 16, 197), 4, 0), ((1, 64, 16, 900), 8, 3),
-                                                   ((2, 64, 16, 100), 5, 0)])
-def test_forward_call_replays_from_a_graph(lb, shape, window, segments):
+@pytest.mark.parametrize("shape,window,segments,mapping", [
+    ((2, 70, 16, 197), 4, 0, 0), ((1, 64, 16, 900), 8, 3, 0), ((2, 64, 16, 100), 5, 0, 0),
+    ((2, 9, 16, 2500), 8, 0, 2),        # the chunk-per-lane kernel
+])
+def test_forward_call_replays_from_a_graph(lb, shape, window, segments, mapping):
     import torch
     from gpu_util import fwd_inputs, to_device
     from paper_2506_15976_amd.inputs import make_inputs
     B, D, N, L = shape
     lib = lb.load()
     lb.lbscan_set_option("segments", segments)
+    lb.lbscan_set_option("mapping", mapping)
     try:
         dev = fwd_inputs(to_device(make_inputs(B, D, N, L, seed=8100 + L), "fp32"))
         y_eager = lb.lbscan_fwd(**dev, window=window)
@@ -65,6 +68,7 @@ def test_forward_call_replays_from_a_graph(lb, shape, window, segments):
             assert torch.equal(again, y_eager)
     finally:
         lb.lbscan_set_option("segments", 0)
+        lb.lbscan_set_option("mapping", 0)
 
 
 def test_backward_call_replays_from_a_graph(lb, oracle):

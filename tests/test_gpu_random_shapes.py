@@ -23,8 +23,11 @@ def _cases():
     n = int(os.environ.get("LBSCAN_RANDOM_CASES", "36"))
     r = np.random.default_rng(int(os.environ.get("LBSCAN_RANDOM_SEED", "20250615")))
     out = []
+    r2 = np.random.default_rng(977)          # (a stream of its own: the cases above stay as they were)
     for i in range(n):
         out.append(dict(
+            # a third of the forward calls go through the chunk-per-lane kernel where it applies
+            mapping=int(r2.choice([0, 0, 2])),
             B=int(r.integers(1, 4)), D=int(r.integers(1, 200)), N=int(r.integers(1, 17)),
             L=int(r.integers(1, 400)), M=int(r.choice([1, 2, 3, 4, 5, 7, 8, 11, 16, 16, 4, 8])),
             reverse=bool(r.integers(0, 2)), dtype="bf16" if r.random() < 0.25 else "fp32",
@@ -52,12 +55,14 @@ def test_random_case(lb, oracle, c):
     h0d = None if h0 is None else torch.from_numpy(h0).cuda()
     dhTd = None if dhT is None else torch.from_numpy(dhT).cuda()
     lb.lbscan_set_option("segments", c["segments"])
+    lb.lbscan_set_option("mapping", c["mapping"])
     try:
         out, hT = lb.lbscan_fwd(**f, window=c["M"], reverse=c["reverse"], h0=h0d, return_state=True)
         g = lb.lbscan_bwd(**f, dout=dev["dout"], window=c["M"], reverse=c["reverse"], h0=h0d, dhT=dhTd)
         torch.cuda.synchronize()
     finally:
         lb.lbscan_set_option("segments", 0)
+        lb.lbscan_set_option("mapping", 0)
     src = flip_time(s) if c["reverse"] else s
     ref, ref_hT = oracle.fwd(**fwd_inputs(src), window=c["M"], h0=h0, return_state=True)
     rg = oracle.bwd(**fwd_inputs(src), dout=src["dout"], window=c["M"], h0=h0, dhT=dhT)
