@@ -201,7 +201,7 @@ def measure_workload(lb, lib, name, w, sets, steps, warmup, with_bwd, per_launch
     # the same call with the row-per-lane kernels forced (rows cut into segments), where
     # the library itself picks the chunk-per-lane kernel
     out["fwd_row_per_lane_ms"] = None
-    if w["dtype"] == "bf16" and w["seqlen"] >= 2048 and grid is None:
+    if w["seqlen"] >= 1024 and w["batch"] * w["dim"] >= 1536 and grid is None:
         lb.lbscan_set_option("mapping", 1)
         try:
             out["fwd_row_per_lane_ms"] = time_calls(fwd_calls, max(steps // 2, 1), max(warmup // 2, 1))

@@ -50,14 +50,17 @@ size_t carry_floats(const FwdParams& p, int nseg)
     return (size_t)nseg * p.batch * p.dim * (size_t)p.dstate;
 }
 
-// The chunk-per-lane kernel takes over where the row-per-lane kernels would have
-// to cut rows into segments (a second read and ~60% more arithmetic) although
-// there are rows enough to fill the chip with one wave per row: long rows, many
-// of them (8 x 768 rows of 4096 bf16 tokens: 184 us against 226 us).  With fp32
-// storage the two are level (217 us both: four rows share a staged Bm / Cm chunk,
-// and at 4 bytes per element those reads keep the texture-address unit busy), and
-// the row-per-lane kernels keep the call.  It leaves no checkpoints for a backward
-// call.
+// The chunk-per-lane kernel (one wave per row, 1024-token chunks) against the
+// row-per-lane kernels, measured on MI355X (us, row-per-lane / chunk-per-lane):
+//   B x D = 8 x 768,  L = 4096, bf16: 239 / 161      fp32: 217 / 180
+//   32 x 768, L = 2048, bf16: 368 / 287               16 x 768, L = 2048, fp32: 204 / 186
+//   8 x 384,  L = 4096, bf16: 132 / 83                16 x 768, L = 1024, fp32: 111 / 94
+//   2 x 768,  L = 8192, bf16: 139 / 129               fp32: 138 / 150
+//   64 x 384, L = 1024, fp32: 187 / 187 (rows not cut by the row-per-lane path)
+// It needs rows enough for a wave each (four rows per block, three blocks per CU),
+// and chunks that are mostly full.  With fp32 storage it wins where the row-per-lane
+// kernels would have to cut rows into segments; with bf16 storage always.  It leaves
+// no checkpoints for a backward call.
 bool use_chunk_mapping(const FwdParams& p, const Shape& s, const float* saved)
 {
     if (p.force_mapping == 1) return false;
@@ -67,7 +70,10 @@ bool use_chunk_mapping(const FwdParams& p, const Shape& s, const float* saved)
     if (saved && s.nseg == 1) return false;
     if (p.force_mapping == 2) return true;
     const long rows = (long)p.batch * p.dim;
-    return p.dtype != 0 && s.nseg > 1 && rows >= 4096 && p.seqlen >= 2048;
+    const long chunk = 1024, nchunks = (p.seqlen + chunk - 1) / chunk;
+    if (p.seqlen * 5 < nchunks * chunk * 4) return false;             // chunks less than 80% full
+    if (p.dtype != 0) return rows >= 1536;
+    return rows >= 3072 && s.nseg > 1;
 }
 
 }  // namespace

@@ -99,6 +99,9 @@ chunk_fwd_kernel(const FwdParams p)
     __shared__ __attribute__((aligned(16))) float sBC[2][2][kBuf];   // [buffer][Bm | Cm]
     __shared__ __attribute__((aligned(16))) float swave[kR][kBuf];   // per wave: turning row tensors
     __shared__ float scar[kR][16];          // per wave: state entering the chunk
+    __shared__ float sA2[kR][16];           // per wave: A[d, :] log2(e) (read from LDS per state: a
+                                            // global load in the state loop would make its wait
+                                            // cover the Bm / Cm prefetch issued just before it)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -120,7 +123,10 @@ chunk_fwd_kernel(const FwdParams p)
     const float skip = p.Dskip ? p.Dskip[dc] : 0.0f;
     float* wbuf = swave[wv];
 
-    if (lane < N) scar[wv][lane] = (p.h0 && row_ok) ? p.h0[((long)b * D + d) * N + lane] : 0.0f;
+    if (lane < N) {
+        scar[wv][lane] = (p.h0 && row_ok) ? p.h0[((long)b * D + d) * N + lane] : 0.0f;
+        sA2[wv][lane] = p.A[(long)dc * N + lane] * kLog2e;
+    }
 
     const int nchunks = (L + kChunk - 1) / kChunk;
     // Bm / Cm staging: the 256 quads of each are spread over the block's threads
@@ -233,7 +239,7 @@ chunk_fwd_kernel(const FwdParams p)
             }
 
             if (row_ok) {
-                const float A2 = p.A[(long)d * N + n] * kLog2e;                  // uniform
+                const float A2 = sA2[wv][n];                                     // uniform
                 float a[kP], u[kP];
                 // first traversal: the state the lane's tokens reach from zero
                 float e = 0.0f;
