@@ -229,7 +229,7 @@ int lbscan_default_window(int32_t seqlen);
  *                 per lane (the tile-per-thread organisation of Sec. 3.4; picked
  *                 for long bf16 rows that are many).  1 forces the first, 2 the
  *                 second wherever it applies (compiled window lengths, stored
- *                 order, reverse = 0, rows that allow 16-byte accesses); other
+ *                 order, rows that allow 16-byte accesses); other
  *                 calls are not affected.  Results agree within the tolerance of
  *                 the arithmetic; workspace sizes do not change.
  * Returns LBSCAN_EINVAL for an unknown name or a value out of range. */

@@ -14,9 +14,10 @@
 // by lane shuffles inside a wave and the state that leaves a chunk carried to the
 // next in a scalar.  Against the row-per-lane kernel it reads every tensor once
 // and needs no summary pass for long rows, at the price of the second traversal
-// and the prefix scan (about 3 more issue slots per state update) and of Bm / Cm
+// and the prefix scan (about 2 more issue slots per state update) and of Bm / Cm
 // reads per lane instead of per wave; it wins where rows are long and many
-// (4096-token images), and loses where a row is shorter than a few chunks.
+// (4096-token images), and loses where a row is much shorter than a chunk.
+// REV scans the reversed sequence: logical token t is the stored token L-1-t.
 //
 // Bm[b,n,:] and Cm[b,n,:] of the chunk are shared by the kR rows (waves) of a
 // block: they are staged once per state in LDS (double buffered, one barrier per
@@ -91,7 +92,7 @@ __device__ __forceinline__ void wave_scan_affine(float& P, float& e)
 // Quad q (tokens 4q .. 4q+3 of the chunk) lands where lane q / 4 reads its tokens from.
 __device__ __forceinline__ int quad_slot(int q) { return (q >> 2) * kPitch + 4 * (q & 3); }
 
-template <typename T, int M>
+template <typename T, int M, bool REV>
 __global__ void __launch_bounds__(64 * kR, LBSCAN_CHUNK_MINBLOCKS)
 chunk_fwd_kernel(const FwdParams p)
 {
@@ -136,6 +137,20 @@ chunk_fwd_kernel(const FwdParams p)
     // (whether a chunk lies inside the row is decided once per chunk, for all lanes:
     // per-quad checks would put every load behind a branch of its own)
     auto chunk_is_whole = [&](int chunk) { return (chunk + 1) * kChunk <= L; };
+    // The quad of logical tokens t0 .. t0+3 of a row tensor.  REV: logical token t is the
+    // stored token L-1-t (the scan runs over the reversed sequence), i.e. the stored
+    // quad that ends at L-t0, its elements in opposite order.
+    auto fetch_quad = [&](const T* __restrict__ src, int t0, bool whole) {
+        const int ph = REV ? L - 4 - t0 : t0;
+        Quad<T> q;
+        if (whole) q = quad_raw_fast<T>(src, ph);
+        else q = quad_raw_checked<T>(src, ph, ph, L);
+        if (REV) {
+            const T a = q.v[0], b2 = q.v[1];
+            q.v[0] = q.v[3]; q.v[1] = q.v[2]; q.v[2] = b2; q.v[3] = a;
+        }
+        return q;
+    };
     auto load_bc = [&](int chunk, int n) {
         BCQuads r;
         const bool whole = chunk_is_whole(chunk);
@@ -145,8 +160,7 @@ chunk_fwd_kernel(const FwdParams p)
 #pragma unroll
             for (int j = 0; j < kBCQ; ++j) {
                 const int t0 = chunk * kChunk + 4 * (tid + 64 * kR * j);
-                if (whole) r.q[w][j] = quad_raw_fast<T>(src, t0);
-                else r.q[w][j] = quad_raw_checked<T>(src, t0, t0, L);
+                r.q[w][j] = fetch_quad(src, t0, whole);
             }
         }
         return r;
@@ -170,8 +184,7 @@ chunk_fwd_kernel(const FwdParams p)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int t0 = chunk * kChunk + 4 * (lane + 64 * j);
-            if (whole) r.q[j] = quad_raw_fast<T>(src, t0);
-            else r.q[j] = quad_raw_checked<T>(src, t0, t0, L);
+            r.q[j] = fetch_quad(src, t0, whole);
         }
         return r;
     };
@@ -329,7 +342,12 @@ chunk_fwd_kernel(const FwdParams p)
                 const int t0 = chunk * kChunk + 4 * q;
                 float v[4];
                 lds_get4(wbuf, quad_slot(q), v);
-                quad_store<T>(yg, t0, whole, t0, L, v);
+                if (REV) {
+                    const float a = v[0], b2 = v[1];
+                    v[0] = v[3]; v[1] = v[2]; v[2] = b2; v[3] = a;
+                }
+                const int ph = REV ? L - 4 - t0 : t0;
+                quad_store<T>(yg, ph, whole, ph, L, v);
             }
         }
     }
@@ -345,14 +363,18 @@ hipError_t launch_chunk_t(const FwdParams& p, hipStream_t s)
     const long nblocks = (long)((p.dim + kR - 1) / kR) * p.batch;
     if (nblocks > 0x7fffffffL) return hipErrorInvalidConfiguration;
     dim3 grid((unsigned)nblocks), block(64 * kR);
+#define LBSCAN_LAUNCH_CHUNK(M)                                                              \
+    if (p.reverse) hipLaunchKernelGGL((chunk_fwd_kernel<T, M, true>), grid, block, 0, s, p);   \
+    else hipLaunchKernelGGL((chunk_fwd_kernel<T, M, false>), grid, block, 0, s, p)
     switch (p.window) {
-        case 1:  hipLaunchKernelGGL((chunk_fwd_kernel<T, 1>), grid, block, 0, s, p); break;
-        case 2:  hipLaunchKernelGGL((chunk_fwd_kernel<T, 2>), grid, block, 0, s, p); break;
-        case 4:  hipLaunchKernelGGL((chunk_fwd_kernel<T, 4>), grid, block, 0, s, p); break;
-        case 8:  hipLaunchKernelGGL((chunk_fwd_kernel<T, 8>), grid, block, 0, s, p); break;
-        case 16: hipLaunchKernelGGL((chunk_fwd_kernel<T, 16>), grid, block, 0, s, p); break;
+        case 1:  LBSCAN_LAUNCH_CHUNK(1); break;
+        case 2:  LBSCAN_LAUNCH_CHUNK(2); break;
+        case 4:  LBSCAN_LAUNCH_CHUNK(4); break;
+        case 8:  LBSCAN_LAUNCH_CHUNK(8); break;
+        case 16: LBSCAN_LAUNCH_CHUNK(16); break;
         default: return hipErrorInvalidValue;
     }
+#undef LBSCAN_LAUNCH_CHUNK
     return hipGetLastError();
 }
 
@@ -360,9 +382,9 @@ hipError_t launch_chunk_t(const FwdParams& p, hipStream_t s)
 
 bool fwd_chunk_supported(const FwdParams& p)
 {
-    // stored order, left to right, rows that allow quad accesses, nothing that only
-    // the row-per-lane kernels produce (checkpoints, first-pass partials)
-    if (!window_supported(p.window) || p.reverse || p.order.kind != 0) return false;
+    // stored order (either direction), rows that allow quad accesses, nothing that
+    // only the row-per-lane kernels produce (checkpoints, first-pass partials)
+    if (!window_supported(p.window) || p.order.kind != 0) return false;
     if (p.yprev || p.y_is_f32 || p.ckpt || p.summary_only || p.generic_window) return false;
     if (p.dtype != 0 && (p.seqlen & 1)) return false;
     return p.dstate >= 1 && p.dstate <= 16;

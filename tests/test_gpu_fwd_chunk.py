@@ -23,13 +23,16 @@ def chunk_mapping(lb):
     lb.lbscan_set_option("mapping", 0)
 
 
-def _run_fwd(lb, oracle, s, *, window, dtype="fp32", softplus=True):
+def _run_fwd(lb, oracle, s, *, window, dtype="fp32", softplus=True, reverse=False):
     import torch
-    from gpu_util import assert_close, fwd_inputs, to_device, to_numpy
+    from gpu_util import assert_close, flip_time, fwd_inputs, to_device, to_numpy
     dev = to_device(s, dtype)
-    got = lb.lbscan_fwd(**fwd_inputs(dev), window=window, delta_softplus=softplus)
+    got = lb.lbscan_fwd(**fwd_inputs(dev), window=window, delta_softplus=softplus, reverse=reverse)
     torch.cuda.synchronize()
-    ref = oracle.fwd(**fwd_inputs(s), window=window, delta_softplus=softplus)
+    src = flip_time(s) if reverse else s
+    ref = oracle.fwd(**fwd_inputs(src), window=window, delta_softplus=softplus)
+    if reverse:
+        ref = ref[..., ::-1]
     return assert_close(to_numpy(got), ref, dtype)
 
 
@@ -40,6 +43,7 @@ def test_every_compiled_window(lb, oracle, chunk_mapping, window):
     for (B, D, N, L) in [(2, 5, 16, 37), (1, 13, 16, 1500), (2, 8, 16, 1024)]:
         s = make_inputs(B, D, N, L, seed=7100 + D + L, random_A=True)
         _run_fwd(lb, oracle, s, window=window)
+        _run_fwd(lb, oracle, s, window=window, reverse=True)
 
 
 @pytest.mark.parametrize("shape", [
@@ -50,6 +54,7 @@ def test_ragged_shapes_and_small_state_sizes(lb, oracle, chunk_mapping, shape):
     B, D, N, L = shape
     s = make_inputs(B, D, N, L, seed=7200 + D + L, random_A=True)
     _run_fwd(lb, oracle, s, window=4)
+    _run_fwd(lb, oracle, s, window=8, reverse=True)
     s["delta"] = np.abs(s["delta"]) * 0.1          # used as the time step itself
     s["delta_bias"] = np.abs(s["delta_bias"]) * 0.1
     _run_fwd(lb, oracle, s, window=16, softplus=False)
@@ -60,6 +65,7 @@ def test_bf16_storage(lb, oracle, chunk_mapping):
     for (B, D, L, M) in [(2, 12, 1500, 8), (1, 8, 64, 4), (1, 9, 2050, 16)]:
         s = make_inputs(B, D, 16, L, seed=7300 + L, dtype="bf16")
         _run_fwd(lb, oracle, s, window=M, dtype="bf16")
+        _run_fwd(lb, oracle, s, window=M, dtype="bf16", reverse=True)
 
 
 def test_bf16_rows_of_odd_length_fall_back(lb, oracle, chunk_mapping):
@@ -93,6 +99,14 @@ def test_entering_and_leaving_states(lb, oracle, chunk_mapping):
         ref, ref_hT = oracle.fwd(**fwd_inputs(s), window=8, h0=h0, return_state=True)
         assert_close(to_numpy(out), ref, "fp32", "out")
         assert_close(to_numpy(hT), ref_hT, "fp32", "hT")
+        # the reversed sequence: the state enters at the last stored token
+        from gpu_util import flip_time
+        out, hT = lb.lbscan_fwd(**fwd_inputs(dev), window=8, h0=torch.from_numpy(h0).cuda(), return_state=True,
+                                reverse=True)
+        torch.cuda.synchronize()
+        ref, ref_hT = oracle.fwd(**fwd_inputs(flip_time(s)), window=8, h0=h0, return_state=True)
+        assert_close(to_numpy(out), ref[..., ::-1], "fp32", "out, reversed")
+        assert_close(to_numpy(hT), ref_hT, "fp32", "hT, reversed")
 
 
 def test_extreme_time_steps_and_decay_rates(lb, oracle, chunk_mapping):
