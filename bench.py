@@ -446,7 +446,9 @@ def main():
         "metric": "lbscan_fwd_tokens_per_s", "value": tokens / (ms_fwd * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_fwd,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        # the type the path computes in (storage is the workload's: config and "workloads")
+        "dtype": workloads[a.workload]["arithmetic"] if a.workload in workloads else "f32",
+        "storage_dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": f"{a.workload}: B={w['batch']} D={w['dim']} N={w['dstate']} L={w['seqlen']} "
                                f"M={w['window']} {w['dtype']} storage, fp32 arithmetic, forward",
                    "input_sets_rotated": nsets},
