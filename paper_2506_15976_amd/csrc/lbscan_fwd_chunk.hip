@@ -92,7 +92,12 @@ __device__ __forceinline__ void wave_scan_affine(float& P, float& e)
 // Quad q (tokens 4q .. 4q+3 of the chunk) lands where lane q / 4 reads its tokens from.
 __device__ __forceinline__ int quad_slot(int q) { return (q >> 2) * kPitch + 4 * (q & 3); }
 
-template <typename T, int M, bool REV>
+// Four quads of a row tensor of element type U, as loaded (lane l: quads l, l+64, ...).
+template <typename U> struct RowQuads { Quad<U> q[4]; };
+
+// TY: element type of y (the storage type, or float for the first pass of the two-pass
+// global bi-directional scan, which leaves its ungated result in fp32).
+template <typename T, int M, bool REV, typename TY>
 __global__ void __launch_bounds__(64 * kR, LBSCAN_CHUNK_MINBLOCKS)
 chunk_fwd_kernel(const FwdParams p)
 {
@@ -117,7 +122,8 @@ chunk_fwd_kernel(const FwdParams p)
     const T* __restrict__ xg = static_cast<const T*>(p.x) + rowoff;
     const T* __restrict__ dg = static_cast<const T*>(p.delta) + rowoff;
     const T* __restrict__ zg = p.z ? static_cast<const T*>(p.z) + rowoff : nullptr;
-    T* __restrict__ yg = static_cast<T*>(p.y) + rowoff;
+    TY* __restrict__ yg = static_cast<TY*>(p.y) + rowoff;
+    const float* __restrict__ yprevg = p.yprev ? p.yprev + rowoff : nullptr;   // added to y before the gate
     const T* __restrict__ Bg = static_cast<const T*>(p.Bm) + (long)b * N * L;
     const T* __restrict__ Cg = static_cast<const T*>(p.Cm) + (long)b * N * L;
     const float bias = p.bias ? p.bias[dc] : 0.0f;
@@ -140,13 +146,14 @@ chunk_fwd_kernel(const FwdParams p)
     // The quad of logical tokens t0 .. t0+3 of a row tensor.  REV: logical token t is the
     // stored token L-1-t (the scan runs over the reversed sequence), i.e. the stored
     // quad that ends at L-t0, its elements in opposite order.
-    auto fetch_quad = [&](const T* __restrict__ src, int t0, bool whole) {
+    auto fetch_quad = [&](const auto* src, int t0, bool whole) {
+        using U = std::remove_cv_t<std::remove_pointer_t<decltype(src)>>;
         const int ph = REV ? L - 4 - t0 : t0;
-        Quad<T> q;
-        if (whole) q = quad_raw_fast<T>(src, ph);
-        else q = quad_raw_checked<T>(src, ph, ph, L);
+        Quad<U> q;
+        if (whole) q = quad_raw_fast<U>(src, ph);
+        else q = quad_raw_checked<U>(src, ph, ph, L);
         if (REV) {
-            const T a = q.v[0], b2 = q.v[1];
+            const U a = q.v[0], b2 = q.v[1];
             q.v[0] = q.v[3]; q.v[1] = q.v[2]; q.v[2] = b2; q.v[3] = a;
         }
         return q;
@@ -177,9 +184,9 @@ chunk_fwd_kernel(const FwdParams p)
     };
     // one row tensor of the chunk: coalesced quads (issue_row), turned through the
     // wave's LDS buffer into this lane's 16 tokens (turn_row) when they are needed
-    struct RowQuads { Quad<T> q[4]; };
-    auto issue_row = [&](const T* __restrict__ src, int chunk) {
-        RowQuads r;
+    auto issue_row = [&](const auto* src, int chunk) {
+        using U = std::remove_cv_t<std::remove_pointer_t<decltype(src)>>;
+        RowQuads<U> r;
         const bool whole = chunk_is_whole(chunk);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -188,7 +195,7 @@ chunk_fwd_kernel(const FwdParams p)
         }
         return r;
     };
-    auto turn_row = [&](const RowQuads& r, float (&out)[kP]) {
+    auto turn_row = [&](const auto& r, float (&out)[kP]) {
         wave_sync_lds();                              // earlier readers of wbuf are done
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -212,7 +219,7 @@ chunk_fwd_kernel(const FwdParams p)
     // and its x while that chunk's result is stored; z during the chunk's own last state
     // (fp32 quads are twice the registers: there the time steps wait for the store phase too)
     constexpr bool kEarlyDt = sizeof(T) == 2;
-    RowQuads qd = issue_row(dg, 0), qx = issue_row(xg, 0), qz;
+    RowQuads<T> qd = issue_row(dg, 0), qx = issue_row(xg, 0), qz;
     for (int chunk = 0; chunk < nchunks; ++chunk) {
         const int t_lane = chunk * kChunk + lane * kP;          // this lane's first token
         float dt[kP], dx[kP], y[kP];
@@ -317,7 +324,13 @@ chunk_fwd_kernel(const FwdParams p)
         for (int n = 0; n < N - 1; ++n) state_step(n, std::false_type{});
         state_step(N - 1, std::true_type{});
 
-        // gate and store
+        // the result of an earlier pass (two-pass scan), gate, store
+        if (yprevg) {
+            float pv[kP];
+            turn_row(issue_row(yprevg, chunk), pv);
+#pragma unroll
+            for (int k = 0; k < kP; ++k) y[k] += pv[k];
+        }
         if (zg) {
             float zv[kP];
             turn_row(qz, zv);
@@ -347,7 +360,7 @@ chunk_fwd_kernel(const FwdParams p)
                     v[0] = v[3]; v[1] = v[2]; v[2] = b2; v[3] = a;
                 }
                 const int ph = REV ? L - 4 - t0 : t0;
-                quad_store<T>(yg, ph, whole, ph, L, v);
+                quad_store<TY>(yg, ph, whole, ph, L, v);
             }
         }
     }
@@ -363,9 +376,16 @@ hipError_t launch_chunk_t(const FwdParams& p, hipStream_t s)
     const long nblocks = (long)((p.dim + kR - 1) / kR) * p.batch;
     if (nblocks > 0x7fffffffL) return hipErrorInvalidConfiguration;
     dim3 grid((unsigned)nblocks), block(64 * kR);
-#define LBSCAN_LAUNCH_CHUNK(M)                                                              \
-    if (p.reverse) hipLaunchKernelGGL((chunk_fwd_kernel<T, M, true>), grid, block, 0, s, p);   \
-    else hipLaunchKernelGGL((chunk_fwd_kernel<T, M, false>), grid, block, 0, s, p)
+#define LBSCAN_LAUNCH_CHUNK(M)                                                                 \
+    if (p.reverse) hipLaunchKernelGGL((chunk_fwd_kernel<T, M, true, T>), grid, block, 0, s, p);   \
+    else hipLaunchKernelGGL((chunk_fwd_kernel<T, M, false, T>), grid, block, 0, s, p)
+    if (p.y_is_f32 && p.dtype != 0) {
+        // fp32 result from bf16 inputs: the plain scan only (first pass of the two-pass scan)
+        if (p.window != 1) return hipErrorInvalidValue;
+        if (p.reverse) hipLaunchKernelGGL((chunk_fwd_kernel<T, 1, true, float>), grid, block, 0, s, p);
+        else hipLaunchKernelGGL((chunk_fwd_kernel<T, 1, false, float>), grid, block, 0, s, p);
+        return hipGetLastError();
+    }
     switch (p.window) {
         case 1:  LBSCAN_LAUNCH_CHUNK(1); break;
         case 2:  LBSCAN_LAUNCH_CHUNK(2); break;
@@ -385,7 +405,8 @@ bool fwd_chunk_supported(const FwdParams& p)
     // stored order (either direction), rows that allow quad accesses, nothing that
     // only the row-per-lane kernels produce (checkpoints, first-pass partials)
     if (!window_supported(p.window) || p.order.kind != 0) return false;
-    if (p.yprev || p.y_is_f32 || p.ckpt || p.summary_only || p.generic_window) return false;
+    if (p.ckpt || p.summary_only || p.generic_window) return false;
+    if (p.y_is_f32 && p.dtype != 0 && p.window != 1) return false;
     if (p.dtype != 0 && (p.seqlen & 1)) return false;
     return p.dstate >= 1 && p.dstate <= 16;
 }

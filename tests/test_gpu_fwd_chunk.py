@@ -121,6 +121,26 @@ def test_extreme_time_steps_and_decay_rates(lb, oracle, chunk_mapping):
     _run_fwd(lb, oracle, s, window=16)
 
 
+def test_two_pass_comparison_and_any_window_through_this_kernel(lb, oracle, chunk_mapping):
+    """The global bi-directional comparison (window-1 scan left to right into fp32, then
+    right to left on top of it) and the first pass of the any-window path take the same
+    kernel when it applies."""
+    import torch
+    from gpu_util import assert_close, fwd_inputs, to_device, to_numpy
+    from paper_2506_15976_amd.inputs import make_inputs
+    for dtype, (B, D, L) in (("fp32", (2, 9, 1500)), ("bf16", (1, 12, 2050)), ("fp32", (1, 5, 100))):
+        sf = make_inputs(B, D, 16, L, seed=7700 + L, dtype=dtype, random_A=True)
+        sb = make_inputs(B, D, 16, L, seed=7701 + L, dtype=dtype, random_A=True)
+        sb["z"] = sf["z"]
+        df, db = to_device(sf, dtype), to_device(sb, dtype)
+        got = lb.lbscan_bidir_fwd(fwd_inputs(df), fwd_inputs(db))
+        torch.cuda.synchronize()
+        assert_close(to_numpy(got), oracle.bidir_fwd(fwd_inputs(sf), fwd_inputs(sb)), dtype, "bidir")
+        got = lb.lbscan_fwd(**fwd_inputs(df), window=5)
+        torch.cuda.synchronize()
+        assert_close(to_numpy(got), oracle.fwd(**fwd_inputs(sf), window=5), dtype, "window 5")
+
+
 def test_matches_row_per_lane_kernels_at_full_size(lb, oracle):
     """The 4096-token workload in the launch the library picks by itself (this kernel)
     against the oracle, and against the row-per-lane path forced on the same inputs."""
