@@ -1,4 +1,5 @@
-// Forward kernel, "chunk per lane" mapping, for long rows with plenty of rows.
+// Forward kernel, "chunk per lane" mapping, for rows of about a thousand tokens and
+// more when there are rows enough to give each a wave.
 //
 // One wave owns one (batch, channel) row; each lane owns kP = 16 consecutive tokens
 // of a 1024-token chunk and keeps them in registers.  Per state n the lane scans
@@ -11,8 +12,8 @@
 // tokens, so no window leaves a lane.  This is the organisation the paper
 // describes for its own kernel (Sec. 3.4: a tile of tokens per thread, partial
 // results exchanged between threads, a second traversal), with the exchange done
-// by lane shuffles inside a wave and the state that leaves a chunk carried to the
-// next in a scalar.  Against the row-per-lane kernel it reads every tensor once
+// by DPP inside a wave and the state that leaves a chunk carried to the next
+// through one LDS word per state.  Against the row-per-lane kernel it reads every tensor once
 // and needs no summary pass for long rows, at the price of the second traversal
 // and the prefix scan (about 2 more issue slots per state update) and of Bm / Cm
 // reads per lane instead of per wave; it wins where rows are long and many
