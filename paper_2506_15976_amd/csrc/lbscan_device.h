@@ -90,8 +90,9 @@ template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v)
 
 // Four consecutive elements.  Global memory on gfx950 serves multi-dword
 // accesses at dword alignment, so the fp32 quad only promises 4-byte alignment
-// (rows of odd length start at any dword); the bf16 quad promises 4 bytes too
-// and callers fall back to element loads when a row can start at an odd element.
+// (rows of odd length start at any dword); the bf16 quad promises 4 bytes too:
+// where a row can start at an odd element callers use quad_raw_unaligned /
+// quad_store_unaligned inside the row and element accesses at its ragged end.
 template <typename T> struct Quad;
 template <> struct __attribute__((packed, aligned(4))) Quad<float> { float v[4]; };
 template <> struct __attribute__((packed, aligned(4))) Quad<bf16_t> { bf16_t v[4]; };
@@ -129,6 +130,56 @@ template <typename T>
 __device__ __forceinline__ Quad<T> quad_raw_fast(const T* __restrict__ base, long off)
 {
     return *reinterpret_cast<const Quad<T>*>(base + off);
+}
+
+// Four consecutive 2-byte elements at ANY element address (rows of odd length start at
+// odd elements every other row, where a 4-byte access is not allowed): the three
+// aligned dwords around them are loaded and shifted by 16 bits where the address is
+// odd.  Branch-free, so lanes of either parity share the instructions.  The load
+// covers the 12 bytes from the address rounded down to 4: the caller guarantees that
+// they lie inside the tensor (one element before an odd address always does; up to
+// two elements after the quad must).
+__device__ __forceinline__ Quad<bf16_t> quad_raw_unaligned(const bf16_t* __restrict__ p)
+{
+    struct __attribute__((packed, aligned(4))) Words3 { uint32_t v[3]; };
+    const uintptr_t u = reinterpret_cast<uintptr_t>(p);
+    const Words3 w = *reinterpret_cast<const Words3*>(u & ~static_cast<uintptr_t>(3));
+    const uint32_t sh = (static_cast<uint32_t>(u) & 2u) * 8u;           // 0 or 16
+    const uint32_t lo = __builtin_amdgcn_alignbit(w.v[1], w.v[0], sh);
+    const uint32_t hi = __builtin_amdgcn_alignbit(w.v[2], w.v[1], sh);
+    Quad<bf16_t> q;
+    q.v[0].bits = (uint16_t)lo; q.v[1].bits = (uint16_t)(lo >> 16);
+    q.v[2].bits = (uint16_t)hi; q.v[3].bits = (uint16_t)(hi >> 16);
+    return q;
+}
+// (fp32 rows need no such path; the overload keeps templates uniform)
+__device__ __forceinline__ Quad<float> quad_raw_unaligned(const float* __restrict__ p)
+{
+    return *reinterpret_cast<const Quad<float>*>(p);
+}
+// The matching store: 2 + 4 + 2 bytes at an odd element address, 8 bytes at an even one.
+__device__ __forceinline__ void quad_store_unaligned(bf16_t* __restrict__ p, const float in[4])
+{
+    bf16_t e[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) e[k] = from_f32<bf16_t>(in[k]);
+    if (reinterpret_cast<uintptr_t>(p) & 2u) {
+        p[0] = e[0];
+        *reinterpret_cast<uint32_t*>(p + 1) = (uint32_t)e[1].bits | ((uint32_t)e[2].bits << 16);
+        p[3] = e[3];
+    } else {
+        Quad<bf16_t> q;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) q.v[k] = e[k];
+        *reinterpret_cast<Quad<bf16_t>*>(p) = q;
+    }
+}
+__device__ __forceinline__ void quad_store_unaligned(float* __restrict__ p, const float in[4])
+{
+    Quad<float> q;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) q.v[k] = in[k];
+    *reinterpret_cast<Quad<float>*>(p) = q;
 }
 
 template <typename T> __device__ __forceinline__ T zero_elem();

@@ -82,6 +82,22 @@ def test_gradients_bf16_storage(lb, oracle):
         _run_bwd(lb, oracle, s, window=8, dtype="bf16")
 
 
+@pytest.mark.parametrize("L", [197, 193, 49])
+def test_gradients_bf16_rows_of_odd_length(lb, oracle, L):
+    """bf16 rows of odd length: the unaligned quad path of the tiles inside the rows,
+    element accesses at the ragged tile and at the end of the last batch entry."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(3, 70, 16, L, seed=3400 + L, dtype="bf16", with_dout=True, random_A=True)
+    for window in (4, 7):
+        _run_bwd(lb, oracle, s, window=window, dtype="bf16")
+        _run_bwd(lb, oracle, s, window=window, dtype="bf16", reverse=True)
+    lb.lbscan_set_option("segments", 2)
+    try:
+        _run_bwd(lb, oracle, s, window=4, dtype="bf16")
+    finally:
+        lb.lbscan_set_option("segments", 0)
+
+
 @pytest.mark.parametrize("segments", [2, 3, 5])
 def test_gradients_with_rows_cut_into_segments(lb, oracle, segments):
     """Long rows are cut into segments in the backward pass too: forward carry

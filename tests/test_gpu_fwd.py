@@ -245,6 +245,25 @@ def test_bf16_storage_small(lb, oracle):
         _run_fwd(lb, oracle, s, window=4, dtype="bf16", reverse=True)
 
 
+@pytest.mark.parametrize("L", [197, 193, 225, 65, 37])
+def test_bf16_rows_of_odd_length(lb, oracle, L):
+    """bf16 rows of odd length start at odd elements every other row: tiles inside the
+    row go through the unaligned quad path (not allowed to reach past the tensor: the
+    last batch entry's end tile keeps element accesses), ragged tiles through element
+    loads.  Several batch entries, partial row blocks, both directions, rows cut."""
+    from paper_2506_15976_amd.inputs import make_inputs
+    s = make_inputs(3, 70, 16, L, seed=3300 + L, dtype="bf16", random_A=True)
+    for window in (4, 8, 1):
+        _run_fwd(lb, oracle, s, window=window, dtype="bf16")
+        _run_fwd(lb, oracle, s, window=window, dtype="bf16", reverse=True)
+    lb.lbscan_set_option("segments", 3)
+    try:
+        _run_fwd(lb, oracle, s, window=4, dtype="bf16")
+        _run_fwd(lb, oracle, s, window=4, dtype="bf16", reverse=True)
+    finally:
+        lb.lbscan_set_option("segments", 0)
+
+
 @pytest.mark.parametrize("name", ["vim_tiny", "vim_small", "hires_4096", "wsi_bag"])
 def test_full_size_workloads(lb, oracle, name):
     from paper_2506_15976_amd.inputs import WORKLOADS, make_workload
