@@ -76,7 +76,7 @@ def test_without_bias_and_without_activation(lb, oracle):
     _check(lb, oracle, _inputs(2, 6, 130, 4, 6301), activation=False)
 
 
-@pytest.mark.parametrize("L", [96, 197])   # odd row length: rows start at odd bf16 elements
+@pytest.mark.parametrize("L", [96, 197, 5, 7, 261, 1025])   # odd row length: rows start at odd bf16 elements
 def test_bf16_storage(lb, oracle, L):
     _check(lb, oracle, _inputs(2, 8, L, 4, 6400 + L, dtype="bf16"), dtype="bf16")
     _check(lb, oracle, _inputs(2, 8, L, 4, 6401 + L, dtype="bf16"), dtype="bf16", reverse=True)
