@@ -52,7 +52,7 @@ size_t carry_floats(const FwdParams& p, int nseg)
 
 // The chunk-per-lane kernel (one wave per row, 1024-token chunks) against the
 // row-per-lane kernels, measured on MI355X (us, row-per-lane / chunk-per-lane):
-//   B x D = 8 x 768,  L = 4096, bf16: 239 / 161      fp32: 217 / 180
+//   B x D = 8 x 768,  L = 4096, bf16: 213 / 161      fp32: 217 / 180
 //   32 x 768, L = 2048, bf16: 368 / 287               16 x 768, L = 2048, fp32: 204 / 186
 //   8 x 384,  L = 4096, bf16: 132 / 83                16 x 768, L = 1024, fp32: 111 / 94
 //   2 x 768,  L = 8192, bf16: 139 / 129               fp32: 138 / 150
