@@ -78,13 +78,12 @@ __device__ __forceinline__ float to_f32(bf16_t v) { return __uint_as_float((uint
 
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
-// round to nearest even; NaN stays NaN
+// round to nearest even; NaN stays NaN (gfx950 converts in hardware, two values per
+// v_cvt_pk_bf16_f32 where the compiler can pair them)
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v)
 {
-    uint32_t u = __float_as_uint(v);
-    uint32_t r = u + 0x7FFFu + ((u >> 16) & 1u);
     bf16_t o;
-    o.bits = (v != v) ? (uint16_t)0x7FC0u : (uint16_t)(r >> 16);
+    o.bits = __builtin_bit_cast(uint16_t, static_cast<__bf16>(v));
     return o;
 }
 
